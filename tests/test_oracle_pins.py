@@ -1,0 +1,303 @@
+"""Pins for the CPU oracle: every check here compares it with something other than itself --
+hand-worked values, exact rational arithmetic, textbook closed forms, numpy library routines,
+or identities the paper states.  No GPU, no product code (only the seeded input generators)."""
+import os
+from fractions import Fraction
+
+import numpy as np
+import pytest
+
+import oracle
+from paper_2311_06281_amd import workloads
+
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden", "eq4_hand_examples.txt")
+
+
+def _golden_cases():
+    cases = []
+    with open(GOLDEN) as f:
+        for line in f:
+            line = line.strip()
+            if not line or line.startswith("#"):
+                continue
+            x0, a, b, x = [part.split() for part in line.split("|")]
+            cases.append((float(x0[0]), [float(v) for v in a], [float(v) for v in b], [float(v) for v in x]))
+    return cases
+
+
+# ------------------------------------------------------------------ hand-worked values (Sec. 3, Eq. 4)
+@pytest.mark.parametrize("case", _golden_cases())
+def test_hand_examples_sequential(case):
+    x0, a, b, x = case
+    got = oracle.seq_f64(a, b, x0)
+    assert got.tolist() == x  # small dyadic rationals: exact
+
+
+@pytest.mark.parametrize("case", _golden_cases())
+def test_hand_examples_logspace(case):
+    x0, a, b, x = case
+    got, logx = oracle.logspace(a, b, x0)
+    np.testing.assert_allclose(got, x, rtol=0, atol=1e-13 * max(1.0, max(abs(v) for v in x)))
+
+
+@pytest.mark.parametrize("case", _golden_cases())
+def test_hand_examples_batched_entry(case):
+    x0, a, b, x = case
+    n = len(a)
+    for layout, shp in ((oracle.LAYOUT_BDN, (1, 1, n)), (oracle.LAYOUT_BND, (1, n, 1))):
+        got = oracle.sequential(np.array(a, np.float32).reshape(shp), np.array(b, np.float32).reshape(shp),
+                                np.array([x0], np.float32), layout=layout)
+        assert got.reshape(-1).tolist() == x
+
+
+# ------------------------------------------------------------------ exact rationals, Eq. (4), n <= 16
+def _eq4_exact(a, b, x0):
+    """x_k = (prod_{t<=k} a_t) (x0 + sum_{j<=k} b_j / prod_{t<=j} a_t) in exact rationals."""
+    out = []
+    for k in range(1, len(a) + 1):
+        prod_k = Fraction(1)
+        for t in range(k):
+            prod_k *= a[t]
+        acc = Fraction(x0)
+        for j in range(1, k + 1):
+            pj = Fraction(1)
+            for t in range(j):
+                pj *= a[t]
+            acc += Fraction(b[j - 1]) / pj
+        out.append(prod_k * acc)
+    return out
+
+
+def _dyadic(rng, size, nonzero):
+    # multiples of 1/8 in [-2, 2]; exactly representable in float32
+    k = rng.integers(-16, 17, size)
+    if nonzero:
+        k[k == 0] = 3
+    return [Fraction(int(v), 8) for v in k]
+
+
+@pytest.mark.parametrize("n", list(range(1, 17)))
+def test_brute_force_exact_rationals(n):
+    rng = np.random.default_rng(1000 + n)
+    for trial in range(8):
+        a = _dyadic(rng, n, nonzero=True)
+        b = _dyadic(rng, n, nonzero=False)
+        x0 = _dyadic(rng, 1, nonzero=False)[0]
+        if trial == 0:
+            x0 = Fraction(0)
+        if trial == 1:
+            b = [Fraction(0)] * n
+        exact = _eq4_exact(a, b, x0)
+        af = [float(v) for v in a]
+        bf = [float(v) for v in b]
+        got = oracle.seq_f64(af, bf, float(x0))
+        # the running magnitude bounds the rounding error of an n-step float64 recurrence
+        run = 0.0
+        for t in range(n):
+            run = max(run, abs(float(exact[t])), abs(bf[t]))
+            assert abs(got[t] - float(exact[t])) <= 4e-16 * (t + 1) * max(run, 1e-300) * 8
+        if n <= 5:  # 4-bit mantissas, <= 5 factors: every intermediate is exact in float64
+            assert [Fraction(v) for v in got.tolist()] == exact
+        # the closed form (O2) against the same exact values
+        x2, logx = oracle.logspace(af, bf, float(x0))
+        scale = max(max(abs(float(e)) for e in exact), 1.0)
+        # terms b_j / prod a can be much larger than x itself: allow for that cancellation
+        amp = max(abs(float(b[j] / np.prod([float(v) for v in a[: j + 1]]))) for j in range(n)) if n else 1.0
+        prodmax = max(abs(float(np.prod(af[:k]))) for k in range(1, n + 1))
+        tol = 1e-12 * max(scale, amp * prodmax, 1.0)
+        np.testing.assert_allclose(x2, [float(e) for e in exact], rtol=0, atol=tol)
+
+
+def test_recurrence_with_zero_coefficient_restarts():
+    # a_t = 0 forgets the history: x_t = b_t (definition, Sec. 3)
+    a = [0.5, 0.0, 2.0]
+    b = [1.0, 7.0, 1.0]
+    got = oracle.seq_f64(a, b, 4.0)
+    assert got.tolist() == [3.0, 7.0, 15.0]
+
+
+# ------------------------------------------------------------------ closed forms
+@pytest.mark.parametrize("a,b,x0", [(0.9, 0.3, 2.0), (-0.7, 1.1, -0.5), (1.01, -0.2, 3.0), (0.5, 0.0, 1.0)])
+def test_geometric_closed_form(a, b, x0):
+    n = 200
+    t = np.arange(1, n + 1, dtype=np.float64)
+    want = a ** t * x0 + b * (1 - a ** t) / (1 - a)
+    np.testing.assert_allclose(oracle.seq_f64(np.full(n, a), np.full(n, b), x0), want, rtol=1e-12, atol=1e-13)
+    x2, _ = oracle.logspace(np.full(n, a), np.full(n, b), x0)
+    np.testing.assert_allclose(x2, want, rtol=1e-9, atol=1e-11)
+    a32 = np.full((1, 1, n), a, np.float32)
+    b32 = np.full((1, 1, n), b, np.float32)
+    af, bf = float(a32[0, 0, 0]), float(b32[0, 0, 0])
+    want32 = af ** t * np.float32(x0) + bf * (1 - af ** t) / (1 - af)
+    got = oracle.sequential(a32, b32, np.array([x0], np.float32), layout=oracle.LAYOUT_BDN).reshape(-1)
+    np.testing.assert_allclose(got, want32, rtol=1e-12, atol=1e-13)
+
+
+def test_b_zero_is_running_product():
+    rng = np.random.default_rng(7)
+    a = rng.uniform(-1.5, 1.5, 300)
+    want = 0.75 * np.cumprod(a)
+    np.testing.assert_allclose(oracle.seq_f64(a, np.zeros(300), 0.75), want, rtol=1e-13)
+    x2, _ = oracle.logspace(a, np.zeros(300), 0.75)
+    np.testing.assert_allclose(x2, want, rtol=1e-10)
+
+
+def test_a_one_is_running_sum():
+    rng = np.random.default_rng(8)
+    b = rng.normal(0, 1, 500)
+    want = -2.0 + np.cumsum(b)
+    np.testing.assert_allclose(oracle.seq_f64(np.ones(500), b, -2.0), want, rtol=0, atol=1e-12)
+    x2, _ = oracle.logspace(np.ones(500), b, -2.0)
+    np.testing.assert_allclose(x2, want, rtol=0, atol=1e-10)
+
+
+def test_first_output_is_x1_not_x0():
+    # tail() drops log x_0: the first emitted value is a_1 x_0 + b_1 (Sec. 4; Eq. (4) first line)
+    got = oracle.seq_f64([3.0, 2.0], [0.25, 1.0], 5.0)
+    assert got[0] == 15.25 and got.shape == (2,)
+    x2, _ = oracle.logspace([3.0, 2.0], [0.25, 1.0], 5.0)
+    assert abs(x2[0] - 15.25) < 1e-13 and x2.shape == (2,)
+
+
+# ------------------------------------------------------------------ LCSE step against numpy
+def test_lcse_matches_numpy_logaddexp_accumulate():
+    rng = np.random.default_rng(9)
+    z = rng.normal(0, 30, 1000)
+    got = oracle.lcse(z.astype(np.complex128))
+    np.testing.assert_allclose(got.real, np.logaddexp.accumulate(z), rtol=1e-13, atol=1e-13)
+    np.testing.assert_allclose(got.imag, 0, atol=0)
+
+
+def test_lcse_complex_terms_match_linear_cumsum():
+    rng = np.random.default_rng(10)
+    v = rng.normal(0, 1, 40)  # signed linear values, well scaled
+    z = np.log(np.abs(v)) + 1j * np.pi * (v < 0)
+    got = np.exp(oracle.lcse(z))
+    np.testing.assert_allclose(got.real, np.cumsum(v), rtol=0, atol=1e-12)
+    np.testing.assert_allclose(got.imag, 0, atol=1e-12)
+
+
+def test_lcse_handles_minus_infinity_terms():
+    z = np.array([-np.inf, -np.inf, 0.0, -np.inf], dtype=np.complex128)
+    got = oracle.lcse(z)
+    assert got.real.tolist() == [-np.inf, -np.inf, 0.0, 0.0]
+
+
+# ------------------------------------------------------------------ O2 == O1 on every workload distribution
+SMALL = {1: dict(n=4096), 2: dict(B=2, D=8, n=512), 3: dict(n=1 << 16), 4: dict(B=2, D=8, n=512),
+         5: dict(B=2, D=8, n=1024)}
+
+
+def _channels(cfg, batch):
+    """Yield (a, b, x0) float64 vectors per channel."""
+    a, b = batch.a, batch.b
+    if cfg.layout == "BND":
+        a = np.transpose(a, (0, 2, 1))
+        b = np.transpose(b, (0, 2, 1))
+    B, D, n = a.shape
+    for bi in range(B):
+        for d in range(D):
+            x0 = batch.x0[0] if cfg.x0_scalar else batch.x0[bi * D + d]
+            yield bi, d, a[bi, d].astype(np.float64), b[bi, d].astype(np.float64), float(x0)
+
+
+@pytest.mark.parametrize("idx", [1, 2, 3, 4, 5])
+def test_closed_form_agrees_with_definition(idx):
+    cfg = workloads.CONFIGS[idx].scaled(**SMALL[idx])
+    batch = workloads.generate(cfg)
+    layout = oracle.LAYOUT_BND if cfg.layout == "BND" else oracle.LAYOUT_BDN
+    if cfg.log_domain:
+        ref_log = oracle.sequential_log(batch.a, batch.b, batch.x0, layout=layout)
+        for bi, d, la, lb, lx0 in _channels(cfg, batch):
+            x2, logx = oracle.logspace(np.exp(la), np.exp(lb), np.exp(lx0))
+            r = ref_log[bi, d] if cfg.layout == "BDN" else ref_log[bi, :, d]
+            np.testing.assert_allclose(logx.real, r, rtol=0, atol=1e-9)
+            np.testing.assert_allclose(logx.imag, 0, atol=0)
+        return
+    ref = oracle.sequential(batch.a, batch.b, batch.x0, layout=layout)
+    for bi, d, a, b, x0 in _channels(cfg, batch):
+        r = ref[bi, d] if cfg.layout == "BDN" else ref[bi, :, d]
+        np.testing.assert_array_equal(r, oracle.seq_f64(a, b, x0))  # batched entry == single-sequence entry
+        x2, logx = oracle.logspace(a, b, x0)
+        runmax = np.maximum.accumulate(np.abs(r))
+        assert np.all(np.abs(x2 - r) <= 1e-9 * runmax + 1e-300)
+        # Sec. 1, last paragraph: every x_t is real, so Im log x_t is a multiple of pi ...
+        # (measured as Im x_t = |x_t| sin(Im log x_t) against the running scale, since the closed
+        #  form cancels large terms wherever |x_t| is small)
+        assert np.all(np.abs(np.sin(logx.imag)) * np.abs(r) <= 1e-9 * runmax)
+        # ... and its parity is the sign of x_t
+        k = np.rint(logx.imag / np.pi).astype(np.int64)
+        big = np.abs(r) > 1e-9 * runmax
+        assert np.array_equal((k[big] % 2) == 1, r[big] < 0)
+
+
+def test_log_domain_definition_matches_linear_definition():
+    cfg = workloads.CONFIGS[4].scaled(B=2, D=4, n=256)
+    batch = workloads.generate(cfg)
+    ref_log = oracle.sequential_log(batch.a, batch.b, batch.x0, layout=oracle.LAYOUT_BDN)
+    lin = oracle.sequential(np.exp(batch.a.astype(np.float64)).astype(np.float32) * 0 + 1, batch.b * 0, batch.x0 * 0 + 1)
+    assert np.all(lin == 1.0)  # sanity of the linear entry on trivial data
+    for bi, d, la, lb, lx0 in _channels(cfg, batch):
+        want = oracle.seq_f64(np.exp(la), np.exp(lb), np.exp(lx0))
+        np.testing.assert_allclose(np.exp(ref_log[bi, d]), want, rtol=1e-12)
+
+
+# ------------------------------------------------------------------ by-parts (Sec. 1, footnote on associativity)
+@pytest.mark.parametrize("k", [1, 63, 64, 65, 255, 256, 257, 999])
+def test_split_invariance(k):
+    rng = np.random.default_rng(11)
+    n = 1000
+    a = rng.uniform(-1.2, 1.2, n)
+    b = rng.normal(0, 1, n)
+    full = oracle.seq_f64(a, b, 0.3)
+    head = oracle.seq_f64(a[:k], b[:k], 0.3)
+    tail = oracle.seq_f64(a[k:], b[k:], head[-1])
+    np.testing.assert_array_equal(np.concatenate([head, tail]), full)
+    h2, _ = oracle.logspace(a[:k], b[:k], 0.3)
+    t2, _ = oracle.logspace(a[k:], b[k:], h2[-1])
+    runmax = np.maximum.accumulate(np.abs(full))
+    assert np.all(np.abs(np.concatenate([h2, t2]) - full) <= 1e-9 * runmax)
+
+
+# ------------------------------------------------------------------ layouts and channel independence
+def test_layouts_are_transposes_and_channels_independent():
+    rng = np.random.default_rng(12)
+    B, D, n = 3, 5, 40
+    a = rng.uniform(-1, 1, (B, D, n)).astype(np.float32)
+    b = rng.normal(0, 1, (B, D, n)).astype(np.float32)
+    x0 = rng.normal(0, 1, B * D).astype(np.float32)
+    r_bdn = oracle.sequential(a, b, x0, layout=oracle.LAYOUT_BDN)
+    r_bnd = oracle.sequential(np.ascontiguousarray(a.transpose(0, 2, 1)), np.ascontiguousarray(b.transpose(0, 2, 1)),
+                              x0, layout=oracle.LAYOUT_BND)
+    np.testing.assert_array_equal(r_bdn, r_bnd.transpose(0, 2, 1))
+    perm = rng.permutation(D)
+    r_perm = oracle.sequential(a[:, perm], b[:, perm], x0.reshape(B, D)[:, perm].reshape(-1), layout=oracle.LAYOUT_BDN)
+    np.testing.assert_array_equal(r_perm, r_bdn[:, perm])
+    # threads only split channels: identical bits
+    r_thr = oracle.sequential(a, b, x0, layout=oracle.LAYOUT_BDN, threads=4)
+    np.testing.assert_array_equal(r_thr, r_bdn)
+    # scalar x0 broadcasts
+    r_sc = oracle.sequential(a, b, np.array([0.5], np.float32), layout=oracle.LAYOUT_BDN)
+    r_full = oracle.sequential(a, b, np.full(B * D, 0.5, np.float32), layout=oracle.LAYOUT_BDN)
+    np.testing.assert_array_equal(r_sc, r_full)
+
+
+# ------------------------------------------------------------------ input generators
+def test_generators_are_seeded_and_sliceable():
+    cfg = workloads.CONFIGS[5].scaled(B=3, D=8, n=64)
+    full = workloads.generate(cfg)
+    again = workloads.generate(cfg)
+    np.testing.assert_array_equal(full.a, again.a)
+    part = workloads.generate(cfg, b_start=1, nb=1)
+    np.testing.assert_array_equal(part.a[0], full.a[1])
+    np.testing.assert_array_equal(part.x0, full.x0[8:16])
+    assert (full.a < 0).mean() > 0.3  # about half negative
+
+
+def test_bf16_rounding_is_nearest_even_and_widening_exact():
+    x = np.array([1.0, 1.00390625, 1.01171875, -3.0, 0.0, 1e-3], np.float32)
+    bits = workloads.f32_to_bf16_bits(x)
+    back = workloads.bf16_bits_to_f32(bits)
+    # 1 + 2^-8 is a tie between 1.0 and 1 + 2^-7 -> even (1.0); 1 + 3*2^-8 ties to 1 + 2^-6
+    assert back[0] == 1.0 and back[1] == 1.0 and back[2] == np.float32(1.015625) and back[3] == -3.0
+    assert np.all(np.abs(back - x) <= np.abs(x) * 2.0 ** -8)
