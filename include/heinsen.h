@@ -1,0 +1,114 @@
+/*
+ * heinsen.h -- C ABI of libheinsen: the first-order linear recurrence
+ *
+ *        x_t = a_t * x_{t-1} + b_t ,  t = 1..n ,  x_0 given            (paper: Abstract; Sec. 3)
+ *
+ * evaluated on one AMD MI355X (gfx950) for B*D independent sequences with the paper's log-space
+ * closed form (Sec. 1 Eq. (1)-(2); stabilised form of Sec. 4):
+ *
+ *        a*_t     = cumsum_t  log a_t
+ *        log x_t  = a*_t + LCSE( cat(log x_0, log b_t - a*_t) )_t ,    LCSE := log cumsum exp
+ *
+ * Both prefix sums are carried by one associative pair so every element crosses HBM once.  Negative
+ * a_t, b_t, x_0 (complex logarithms in the paper, Sec. 1 last paragraph) are carried as a real
+ * logarithm of the magnitude plus a sign bit.
+ *
+ * All data pointers are DEVICE pointers owned by the caller.  Nothing is retained after a call
+ * returns except library-owned scratch memory (see heinsen_release_scratch).  No torch types, no
+ * C++ types, no exceptions cross this boundary.
+ */
+#ifndef HEINSEN_H
+#define HEINSEN_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+/* Memory layout of a, b and out (x0 is always [B, D]).  t below is 0-based; out[t] = x_{t+1}:
+ * the initial value x_0 is an input only and is never written (tail() in Sec. 4). */
+typedef enum {
+    HEINSEN_LAYOUT_BND = 0, /* [B, n, D] channel-contiguous : element (b,t,d) at ((b*n + t)*D + d) */
+    HEINSEN_LAYOUT_BDN = 1  /* [B, D, n] sequence-contiguous: element (b,t,d) at ((b*D + d)*n + t) */
+} heinsen_layout_t;
+
+/* Flag bits. */
+enum {
+    HEINSEN_LOG_INPUTS = 1u << 0, /* a, b, x0 hold natural logs log a_t, log b_t, log x_0 (all quantities
+                                     positive; -inf encodes 0).  Eq. (2) then starts from these logs.  */
+    HEINSEN_LOG_OUTPUT = 1u << 1, /* out receives log x_t (Eq. (1)) instead of x_t (Eq. (3)).  Needs a
+                                     positive domain: LOG_INPUTS or POSITIVE must also be set.          */
+    HEINSEN_IN_BF16    = 1u << 2, /* a and b are stored as bfloat16 (x0 and out stay float32).          */
+    HEINSEN_POSITIVE   = 1u << 3, /* caller promises a_t > 0, b_t >= 0, x_0 >= 0: sign tracking skipped.
+                                     With a negative input the result is unspecified but memory-safe.   */
+    HEINSEN_X0_SCALAR  = 1u << 4  /* x0 points to ONE float32 that is broadcast to all B*D sequences.    */
+};
+
+typedef enum {
+    HEINSEN_OK = 0,
+    HEINSEN_ERR_INVALID_ARG = 1, /* null pointer, non-positive size, size overflow, misaligned pointer,
+                                    unknown layout or flag bit                                           */
+    HEINSEN_ERR_UNSUPPORTED = 2, /* a legal but unimplemented combination (LOG_OUTPUT on a signed domain) */
+    HEINSEN_ERR_ALLOC = 3,       /* scratch memory could not be allocated; nothing was launched          */
+    HEINSEN_ERR_HIP = 4          /* a HIP runtime call failed; see heinsen_last_hip_error()              */
+} heinsen_status_t;
+
+/*
+ * heinsen_scan -- compute x_1..x_n of every sequence (Sec. 3 definition, via Sec. 4's expression).
+ *
+ *   a_or_log_a, b_or_log_b : device, B*D*n elements in `layout`; float32, or bfloat16 with IN_BF16.
+ *                            With LOG_INPUTS they hold natural logarithms.
+ *   x0                     : device, B*D float32 indexed [b*D + d] (or 1 value with X0_SCALAR);
+ *                            log x_0 with LOG_INPUTS.
+ *   out                    : device, B*D*n float32 in `layout`; x_t, or log x_t with LOG_OUTPUT.
+ *                            May be exactly a_or_log_a or b_or_log_b when those are float32 (every tile
+ *                            reads its inputs before it writes; "in situ", Sec. 1); any other overlap
+ *                            is undefined.
+ *   B, D, n                : batch, channels, sequence length; all >= 1 and B*D*n < 2^62.
+ *   layout                 : a heinsen_layout_t value.
+ *   flags                  : OR of the flag bits above.
+ *   stream                 : a hipStream_t (NULL = the default stream).
+ *
+ * Asynchronous: work is enqueued on `stream` and the call returns without synchronising.  The
+ * returned status covers argument validation, scratch allocation and launch errors only.
+ *
+ * Scratch: a grow-only buffer per (device, stream) holds the inter-tile carries.  It is allocated
+ * with hipMalloc on the first call that needs it or needs more (that call may synchronise the
+ * device); later calls of the same or smaller shape allocate nothing.  Calls on different streams
+ * never share scratch.  Kernels leave the scratch clean on completion, so a launch may be replayed.
+ *
+ * Data-dependent conditions are not errors and follow IEEE arithmetic: a NaN input gives NaN from
+ * that step on in that sequence only; a_t = 0 restarts the sequence at b_t; b_t = 0 and x_0 = 0 are
+ * ordinary values; magnitudes beyond float32 give +-inf.  float32 subnormal inputs are read as 0
+ * and subnormal results are written as 0.  Results are bit-reproducible from run to run.
+ *
+ * Returns a heinsen_status_t.
+ */
+int heinsen_scan(const void *a_or_log_a, const void *b_or_log_b, const void *x0, void *out,
+                 int64_t B, int64_t D, int64_t n, int layout, uint32_t flags, void *stream);
+
+/* Static, NUL-terminated description of a heinsen_status_t value (never NULL). */
+const char *heinsen_status_string(int status);
+
+/* The hipError_t of the last failing HIP call made by this thread inside the library
+ * (0 = hipSuccess).  Meaningful after HEINSEN_ERR_HIP or HEINSEN_ERR_ALLOC. */
+int heinsen_last_hip_error(void);
+
+/* Library version, major*10000 + minor*100 + patch. */
+int heinsen_version(void);
+
+/* Frees every cached scratch buffer (synchronises the devices involved).  Optional: call when no
+ * heinsen_scan is in flight, e.g. before unloading the library.  Returns a heinsen_status_t. */
+int heinsen_release_scratch(void);
+
+/* Name of the kernel heinsen_scan would launch for these arguments (for profilers), written as a
+ * NUL-terminated string into buf (at most buflen bytes).  Launches nothing.  Returns a
+ * heinsen_status_t from the same validation heinsen_scan performs (pointers are not checked). */
+int heinsen_kernel_name(int64_t B, int64_t D, int64_t n, int layout, uint32_t flags, char *buf,
+                        int buflen);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* HEINSEN_H */

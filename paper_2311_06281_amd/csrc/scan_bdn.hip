@@ -1,0 +1,519 @@
+// Sequence-contiguous path: a, b, out are [rows, n] with rows = B*D; time runs along the lanes.
+//
+// Two kernels.
+//  * rows_wave: one wave per row for rows that fit 64*ITEMS elements.  Lane i owns ITEMS consecutive
+//    steps, scans them serially, the 64 lane summaries are scanned with DPP, each lane derives the
+//    state at its first step and emits its elements.  No LDS, no barrier, no global scratch.
+//  * tiles: rows longer than that are cut into tiles of NW*64*ITEMS elements, one workgroup per
+//    tile: the same lane and wave scans, wave summaries chained through LDS, tile summaries chained
+//    through global memory.  Tiles of a row are grouped GK at a time; a tile folds the published
+//    summaries of the earlier tiles of its group in a fixed tree (bit-reproducible) onto the state
+//    at the start of the group, which the last tile of the previous group published in float64.
+//
+// What is computed is Sec. 4's expression applied by parts (Sec. 1, footnote on associativity); the
+// arithmetic is in heinsen_math.hpp.
+#include "heinsen_internal.hpp"
+#include "heinsen_math.hpp"
+
+namespace hs {
+namespace {
+
+// ---- lane-level pieces shared by both kernels --------------------------------------------------------
+
+// Loads the lane's ITEMS consecutive inputs starting `start` elements into a row of length n.
+// Steps at or beyond n are replaced by a = 1, b = 0 (which leave the state unchanged).
+template <bool LOG_IN, typename InT, int ITEMS, bool VECIO>
+__device__ __forceinline__ void lane_load(const InT *arow, const InT *brow, int64_t start, int64_t n,
+                                          float (&Av)[ITEMS], float (&Mv)[ITEMS])
+{
+    const float id_a = LOG_IN ? 0.0f : 1.0f;
+    const float id_b = LOG_IN ? -INFINITY : 0.0f;
+    if (VECIO) {
+        constexpr int VL = 16 / (int)sizeof(InT);
+        static_assert(ITEMS % VL == 0, "ITEMS must be a multiple of the vector length");
+        typedef InT vec_t __attribute__((ext_vector_type(VL)));
+#pragma unroll
+        for (int j = 0; j < ITEMS / VL; ++j) {
+            if (start + j * VL < n) { // n is a multiple of VL: a vector is all in or all out
+                vec_t va = *reinterpret_cast<const vec_t *>(arow + start + j * VL);
+                vec_t vb = *reinterpret_cast<const vec_t *>(brow + start + j * VL);
+#pragma unroll
+                for (int i = 0; i < VL; ++i) {
+                    Av[j * VL + i] = widen(va[i]);
+                    Mv[j * VL + i] = widen(vb[i]);
+                }
+            } else {
+#pragma unroll
+                for (int i = 0; i < VL; ++i) {
+                    Av[j * VL + i] = id_a;
+                    Mv[j * VL + i] = id_b;
+                }
+            }
+        }
+    } else {
+#pragma unroll
+        for (int k = 0; k < ITEMS; ++k) {
+            if (start + k < n) {
+                Av[k] = widen(arow[start + k]);
+                Mv[k] = widen(brow[start + k]);
+            } else {
+                Av[k] = id_a;
+                Mv[k] = id_b;
+            }
+        }
+    }
+}
+
+// Encodes and scans the lane's elements serially.  On return Av[k], Mv[k] and bit k of sAw, sMw hold
+// the summary of the lane's steps 0..k; the summary of all ITEMS steps is returned.
+template <bool SIGNED, bool LOG_IN, int ITEMS>
+__device__ __forceinline__ Seg lane_scan(float (&Av)[ITEMS], float (&Mv)[ITEMS], uint32_t &sAw, uint32_t &sMw)
+{
+    static_assert(ITEMS <= 32, "sign bits are kept in one word");
+    sAw = sMw = 0u;
+    Seg run;
+#pragma unroll
+    for (int k = 0; k < ITEMS; ++k) {
+        float la, lb;
+        uint32_t sa, sb;
+        encode<SIGNED, LOG_IN>(Av[k], la, sa);
+        encode<SIGNED, LOG_IN>(Mv[k], lb, sb);
+        if (k == 0) {
+            run = Seg{la, lb, sa, sb};
+        } else {
+            uint32_t sp = SIGNED ? (run.sM ^ sa) : 0u;
+            slae<SIGNED>(run.M + la, sp, lb, sb, run.M, run.sM);
+            run.A += la;
+            if (SIGNED) run.sA ^= sa;
+        }
+        Av[k] = run.A;
+        Mv[k] = run.M;
+        if (SIGNED) {
+            sAw |= (run.sA >> 31) << k;
+            sMw |= (run.sM >> 31) << k;
+        }
+    }
+    return run;
+}
+
+// Emits the lane's elements given the state at the lane's first step.
+template <bool SIGNED, bool LOG_OUT, int ITEMS, bool VECIO>
+__device__ __forceinline__ void lane_emit(float *orow, int64_t start, int64_t n, const State &st,
+                                          const float (&Av)[ITEMS], const float (&Mv)[ITEMS], uint32_t sAw,
+                                          uint32_t sMw)
+{
+    float o[ITEMS];
+#pragma unroll
+    for (int k = 0; k < ITEMS; ++k) {
+        const uint32_t sA = SIGNED ? ((sAw >> k) << 31) : 0u;
+        const uint32_t sM = SIGNED ? ((sMw >> k) << 31) : 0u;
+        o[k] = emit<SIGNED, LOG_OUT>(st, Av[k], sA, Mv[k], sM);
+    }
+    if (VECIO) {
+        typedef float vec_t __attribute__((ext_vector_type(4)));
+#pragma unroll
+        for (int j = 0; j < ITEMS / 4; ++j) {
+            if (start + j * 4 < n) {
+                vec_t v;
+                v[0] = o[j * 4 + 0];
+                v[1] = o[j * 4 + 1];
+                v[2] = o[j * 4 + 2];
+                v[3] = o[j * 4 + 3];
+                *reinterpret_cast<vec_t *>(orow + start + j * 4) = v;
+            }
+        }
+    } else {
+#pragma unroll
+        for (int k = 0; k < ITEMS; ++k)
+            if (start + k < n) orow[start + k] = o[k];
+    }
+}
+
+// ---- one wave per row -------------------------------------------------------------------------------
+
+struct RowsParams {
+    const void *a;
+    const void *b;
+    const float *x0;
+    float *out;
+    int64_t rows, n;
+    int x0_stride;
+};
+
+template <bool SIGNED, bool LOG_IN, bool LOG_OUT, typename InT, int ITEMS, bool VECIO>
+__global__ __launch_bounds__(256) void heinsen_scan_rows_wave(RowsParams p)
+{
+    const int lane = threadIdx.x & 63;
+    const int64_t row = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (row >= p.rows) return; // whole wave leaves together
+    const InT *arow = reinterpret_cast<const InT *>(p.a) + row * p.n;
+    const InT *brow = reinterpret_cast<const InT *>(p.b) + row * p.n;
+    const int64_t start = (int64_t)lane * ITEMS;
+
+    float Av[ITEMS], Mv[ITEMS];
+    uint32_t sAw, sMw;
+    lane_load<LOG_IN, InT, ITEMS, VECIO>(arow, brow, start, p.n, Av, Mv);
+    Seg mine = lane_scan<SIGNED, LOG_IN, ITEMS>(Av, Mv, sAw, sMw);
+    Seg excl = wave_shift_up<SIGNED>(wave_inclusive_scan<SIGNED>(mine));
+
+    State st;
+    encode<SIGNED, LOG_IN>(p.x0[p.x0_stride ? row : 0], st.lx, st.s);
+    st = seg_apply<SIGNED>(st, excl);
+    lane_emit<SIGNED, LOG_OUT, ITEMS, VECIO>(p.out + row * p.n, start, p.n, st, Av, Mv, sAw, sMw);
+}
+
+// ---- tiles with a chained carry ------------------------------------------------------------------------
+
+constexpr int kTileWaves = 4;   // waves per workgroup
+constexpr int kTileItems = 16;  // elements per lane
+constexpr int kTile = kTileWaves * 64 * kTileItems;
+constexpr int kPerLane = 4;     // earlier tiles of the group folded by one lane of wave 0
+constexpr int kGroupK = 64 * kPerLane;
+
+struct TileParams {
+    const void *a;
+    const void *b;
+    const float *x0;
+    float *out;
+    int64_t rows, n;
+    int x0_stride;
+    uint32_t tpr;       // tiles per row
+    uint32_t gpr;       // groups per row
+    uint32_t ntiles;    // rows * tpr
+    uint32_t nflags;    // words in the flag region after the counters
+    uint32_t *counters; // [0] ticket, [1] done
+    uint32_t *agg_flag; // [ntiles]
+    uint32_t *st_flag;  // [rows * gpr]
+    float *agg_A;       // [ntiles]
+    float *agg_M;
+    uint32_t *agg_S;
+    double *st_L;       // [rows * gpr] log2|x| at the start of a group, float64
+    uint32_t *st_S;
+};
+
+struct State64 {
+    double lx;
+    uint32_t s;
+};
+
+// seg_apply with the state kept in float64: only the (small) correction log2(1 +- 2^-|t|) is formed in
+// float32, so a long chain of groups does not accumulate float32 rounding of the state itself.
+template <bool SIGNED>
+__device__ __forceinline__ State64 seg_apply64(const State64 &x, const Seg &g)
+{
+    const double p = x.lx + (double)g.A;
+    const double q = (double)g.M;
+    const uint32_t sp = SIGNED ? (x.s ^ g.sA) : 0u;
+    const double m = fmax(p, q);
+    float t = (float)(p - q);
+    t = (p == q) ? 0.0f : t;
+    float e = exp2_hw(-fabsf(t));
+    State64 r;
+    r.s = 0u;
+    if (SIGNED) {
+        e = u2f(f2u(e) ^ (sp ^ g.sM));
+        r.s = (t >= 0.0f) ? sp : g.sM;
+    }
+    r.lx = m + (double)log2_hw(1.0f + e);
+    return r;
+}
+
+template <bool SIGNED, bool LOG_IN, bool LOG_OUT, typename InT, bool VECIO, bool MULTI>
+__global__ __launch_bounds__(kTileWaves * 64) void heinsen_scan_tiles(TileParams p)
+{
+    constexpr int NW = kTileWaves;
+    constexpr int ITEMS = kTileItems;
+    __shared__ uint32_t s_tile, s_last;
+    __shared__ float lds_A[NW], lds_M[NW];
+    __shared__ uint32_t lds_S[NW];
+    __shared__ float lds_startL;
+    __shared__ uint32_t lds_startS;
+
+    const int lane = threadIdx.x & 63;
+    const int w = threadIdx.x >> 6;
+
+    uint32_t tile = blockIdx.x;
+    if (MULTI) {
+        // tickets: a tile only ever waits for tiles with smaller tickets, which are already running
+        if (threadIdx.x == 0) s_tile = atomicAdd(&p.counters[0], 1u);
+        __syncthreads();
+        tile = s_tile;
+    }
+    const int64_t row = tile / p.tpr;
+    const uint32_t c = tile % p.tpr;
+    const InT *arow = reinterpret_cast<const InT *>(p.a) + row * p.n;
+    const InT *brow = reinterpret_cast<const InT *>(p.b) + row * p.n;
+    const int64_t start = (int64_t)c * kTile + (int64_t)threadIdx.x * ITEMS;
+
+    float Av[ITEMS], Mv[ITEMS];
+    uint32_t sAw, sMw;
+    lane_load<LOG_IN, InT, ITEMS, VECIO>(arow, brow, start, p.n, Av, Mv);
+    Seg mine = lane_scan<SIGNED, LOG_IN, ITEMS>(Av, Mv, sAw, sMw);
+    Seg incl = wave_inclusive_scan<SIGNED>(mine);
+    Seg lane_excl = wave_shift_up<SIGNED>(incl);
+    if (lane == 63) {
+        lds_A[w] = incl.A;
+        lds_M[w] = incl.M;
+        lds_S[w] = (incl.sA >> 31) | (incl.sM >> 30);
+    }
+    __syncthreads();
+
+    // summary of the waves before this one, and (wave 0) of the whole tile, in wave order
+    Seg wave_excl = seg_identity();
+    Seg total = seg_identity();
+#pragma unroll
+    for (int j = 0; j < NW; ++j) {
+        Seg h;
+        h.A = lds_A[j];
+        h.M = lds_M[j];
+        h.sA = SIGNED ? (lds_S[j] << 31) : 0u;
+        h.sM = SIGNED ? ((lds_S[j] << 30) & kSignBit) : 0u;
+        total = (j == 0) ? h : seg_combine<SIGNED>(total, h);
+        if (j + 1 == w) wave_excl = total;
+    }
+
+    if (w == 0) {
+        State64 st;
+        if (!MULTI) {
+            float lx;
+            encode<SIGNED, LOG_IN>(p.x0[p.x0_stride ? row : 0], lx, st.s);
+            st.lx = (double)lx;
+        } else {
+            const uint32_t g = c / kGroupK;
+            const uint32_t r = c % kGroupK;
+            const bool more = c + 1 < p.tpr;
+            if (more && r < kGroupK - 1) {
+                if (lane == 0) {
+                    p.agg_A[tile] = total.A;
+                    p.agg_M[tile] = total.M;
+                    p.agg_S[tile] = (total.sA >> 31) | (total.sM >> 30);
+                }
+                __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent");
+                if (lane == 0) __hip_atomic_store(&p.agg_flag[tile], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            }
+            // lane i folds the summaries of tiles first + i*kPerLane .. + kPerLane - 1 that precede c
+            const uint32_t first = tile - r; // first tile of the group (same row)
+            {
+#pragma unroll
+                for (int j = 0; j < kPerLane; ++j) {
+                    const uint32_t rr = (uint32_t)lane * kPerLane + j;
+                    if (rr < r) {
+                        while (__hip_atomic_load(&p.agg_flag[first + rr], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == 0u)
+                            __builtin_amdgcn_s_sleep(2);
+                    }
+                }
+                if (g > 0 && lane == 63) {
+                    while (__hip_atomic_load(&p.st_flag[row * p.gpr + g], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == 0u)
+                        __builtin_amdgcn_s_sleep(2);
+                }
+                __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
+            }
+            Seg part = seg_identity();
+#pragma unroll
+            for (int j = 0; j < kPerLane; ++j) {
+                const uint32_t rr = (uint32_t)lane * kPerLane + j;
+                Seg h = seg_identity();
+                if (rr < r) {
+                    h.A = p.agg_A[first + rr];
+                    h.M = p.agg_M[first + rr];
+                    const uint32_t s = SIGNED ? p.agg_S[first + rr] : 0u;
+                    h.sA = s << 31;
+                    h.sM = (s << 30) & kSignBit;
+                }
+                part = (j == 0) ? h : seg_combine<SIGNED>(part, h);
+            }
+            Seg fold = wave_inclusive_scan<SIGNED>(part);
+            fold.A = readlane_f(fold.A, 63);
+            fold.M = readlane_f(fold.M, 63);
+            fold.sA = readlane_u(fold.sA, 63);
+            fold.sM = readlane_u(fold.sM, 63);
+
+            if (g == 0) {
+                float lx;
+                encode<SIGNED, LOG_IN>(p.x0[p.x0_stride ? row : 0], lx, st.s);
+                st.lx = (double)lx;
+            } else {
+                st.lx = p.st_L[row * p.gpr + g];
+                st.s = SIGNED ? p.st_S[row * p.gpr + g] : 0u;
+            }
+            if (r > 0) st = seg_apply64<SIGNED>(st, fold);
+            if (more && r == kGroupK - 1) {
+                State64 nx = seg_apply64<SIGNED>(st, total);
+                if (lane == 0) {
+                    p.st_L[row * p.gpr + g + 1] = nx.lx;
+                    p.st_S[row * p.gpr + g + 1] = nx.s;
+                }
+                __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent");
+                if (lane == 0)
+                    __hip_atomic_store(&p.st_flag[row * p.gpr + g + 1], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            }
+        }
+        if (lane == 0) {
+            lds_startL = (float)st.lx;
+            lds_startS = st.s;
+        }
+    }
+    __syncthreads();
+
+    State st;
+    st.lx = lds_startL;
+    st.s = lds_startS;
+    st = seg_apply<SIGNED>(st, seg_combine<SIGNED>(wave_excl, lane_excl));
+    lane_emit<SIGNED, LOG_OUT, ITEMS, VECIO>(p.out + row * p.n, start, p.n, st, Av, Mv, sAw, sMw);
+
+    if (MULTI) {
+        // the last workgroup to finish restores the zeros in the flag region
+        __syncthreads();
+        if (threadIdx.x == 0) {
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent");
+            uint32_t prev = __hip_atomic_fetch_add(&p.counters[1], 1u, __ATOMIC_ACQ_REL, __HIP_MEMORY_SCOPE_AGENT);
+            s_last = (prev == p.ntiles - 1u) ? 1u : 0u;
+        }
+        __syncthreads();
+        if (s_last) {
+            for (uint32_t i = threadIdx.x; i < p.nflags; i += NW * 64) p.agg_flag[i] = 0u; // st_flag follows agg_flag
+            if (threadIdx.x == 0) {
+                p.counters[0] = 0u;
+                p.counters[1] = 0u;
+            }
+        }
+    }
+}
+
+// ---- host side -------------------------------------------------------------------------------------------
+
+constexpr int64_t kRowsWaveMax = 64 * 32; // longest row the one-wave kernel takes
+
+struct BdnPlan {
+    bool wave_kernel;
+    int items;    // wave kernel: elements per lane
+    bool vecio;
+    bool multi;
+    int64_t rows;
+    uint32_t tpr, gpr, ntiles;
+    size_t off_agg_flag, off_st_flag, flag_bytes;
+    size_t off_agg_A, off_agg_M, off_agg_S, off_st_L, off_st_S, data_bytes;
+};
+
+BdnPlan make_plan(const ScanCall &c)
+{
+    BdnPlan pl = {};
+    pl.rows = c.B * c.D;
+    const int64_t vl = c.bf16 ? 8 : 4;
+    auto aligned16 = [](const void *ptr) { return (reinterpret_cast<uintptr_t>(ptr) % 16) == 0; };
+    pl.vecio = aligned16(c.a) && aligned16(c.b) && aligned16(c.out) && (pl.rows == 1 || c.n % vl == 0) &&
+               (c.n % vl == 0);
+    pl.wave_kernel = c.n <= kRowsWaveMax && !(pl.rows < 64 && c.n > 512);
+    if (pl.wave_kernel) {
+        pl.items = c.n > 1024 ? 32 : (c.n > 512 ? 16 : 8);
+        return pl;
+    }
+    pl.tpr = (uint32_t)ceil_div(c.n, kTile);
+    pl.gpr = (uint32_t)ceil_div(pl.tpr, kGroupK);
+    pl.ntiles = (uint32_t)(pl.rows * pl.tpr);
+    pl.multi = pl.tpr > 1;
+    if (!pl.multi) return pl;
+    size_t off = 64;
+    pl.off_agg_flag = off;
+    off += (size_t)pl.ntiles * 4;
+    pl.off_st_flag = off;
+    off += (size_t)pl.rows * pl.gpr * 4;
+    pl.flag_bytes = align_up(off, 256);
+    off = 0;
+    const size_t agg = align_up((size_t)pl.ntiles * 4, 256);
+    pl.off_agg_A = off; off += agg;
+    pl.off_agg_M = off; off += agg;
+    pl.off_agg_S = off; off += agg;
+    pl.off_st_L = off; off += align_up((size_t)pl.rows * pl.gpr * 8, 256);
+    pl.off_st_S = off; off += align_up((size_t)pl.rows * pl.gpr * 4, 256);
+    pl.data_bytes = off;
+    return pl;
+}
+
+template <bool SIGNED, bool LOG_IN, bool LOG_OUT, typename InT>
+hipError_t launch_mode(const ScanCall &c, const BdnPlan &pl, char *flags, char *data)
+{
+    if (pl.wave_kernel) {
+        RowsParams p;
+        p.a = c.a;
+        p.b = c.b;
+        p.x0 = c.x0;
+        p.out = c.out;
+        p.rows = pl.rows;
+        p.n = c.n;
+        p.x0_stride = c.x0_scalar ? 0 : 1;
+        dim3 grid((unsigned)ceil_div(pl.rows, 4)), block(256);
+#define HS_ROWS(ITEMS_, VEC_)                                                                            \
+    hipLaunchKernelGGL((heinsen_scan_rows_wave<SIGNED, LOG_IN, LOG_OUT, InT, ITEMS_, VEC_>), grid, block, 0, \
+                       c.stream, p)
+        if (pl.vecio) {
+            if (pl.items == 32) HS_ROWS(32, true);
+            else if (pl.items == 16) HS_ROWS(16, true);
+            else HS_ROWS(8, true);
+        } else {
+            if (pl.items == 32) HS_ROWS(32, false);
+            else if (pl.items == 16) HS_ROWS(16, false);
+            else HS_ROWS(8, false);
+        }
+#undef HS_ROWS
+        return hipGetLastError();
+    }
+    TileParams p;
+    p.a = c.a;
+    p.b = c.b;
+    p.x0 = c.x0;
+    p.out = c.out;
+    p.rows = pl.rows;
+    p.n = c.n;
+    p.x0_stride = c.x0_scalar ? 0 : 1;
+    p.tpr = pl.tpr;
+    p.gpr = pl.gpr;
+    p.ntiles = pl.ntiles;
+    p.nflags = pl.multi ? (uint32_t)(pl.ntiles + pl.rows * pl.gpr) : 0u;
+    p.counters = reinterpret_cast<uint32_t *>(flags);
+    p.agg_flag = reinterpret_cast<uint32_t *>(flags + pl.off_agg_flag);
+    p.st_flag = reinterpret_cast<uint32_t *>(flags + pl.off_st_flag);
+    p.agg_A = reinterpret_cast<float *>(data + pl.off_agg_A);
+    p.agg_M = reinterpret_cast<float *>(data + pl.off_agg_M);
+    p.agg_S = reinterpret_cast<uint32_t *>(data + pl.off_agg_S);
+    p.st_L = reinterpret_cast<double *>(data + pl.off_st_L);
+    p.st_S = reinterpret_cast<uint32_t *>(data + pl.off_st_S);
+    dim3 grid(pl.ntiles), block(kTileWaves * 64);
+#define HS_TILES(VEC_, MULTI_) \
+    hipLaunchKernelGGL((heinsen_scan_tiles<SIGNED, LOG_IN, LOG_OUT, InT, VEC_, MULTI_>), grid, block, 0, c.stream, p)
+    if (pl.vecio) {
+        if (pl.multi) HS_TILES(true, true);
+        else HS_TILES(true, false);
+    } else {
+        if (pl.multi) HS_TILES(false, true);
+        else HS_TILES(false, false);
+    }
+#undef HS_TILES
+    return hipGetLastError();
+}
+
+hipError_t launch_dispatch(const ScanCall &c, const BdnPlan &pl, char *flags, char *data)
+{
+    HS_DISPATCH_MODE(c, launch_mode, c, pl, flags, data);
+}
+
+} // namespace
+
+ScratchNeed bdn_scratch(const ScanCall &c)
+{
+    BdnPlan pl = make_plan(c);
+    return ScratchNeed{pl.flag_bytes, pl.data_bytes};
+}
+
+hipError_t bdn_launch(const ScanCall &c, void *flags, void *data)
+{
+    BdnPlan pl = make_plan(c);
+    return launch_dispatch(c, pl, static_cast<char *>(flags), static_cast<char *>(data));
+}
+
+const char *bdn_kernel_name(const ScanCall &c)
+{
+    return make_plan(c).wave_kernel ? "heinsen_scan_rows_wave" : "heinsen_scan_tiles";
+}
+
+} // namespace hs
