@@ -1,0 +1,193 @@
+#!/usr/bin/env python3
+"""Benchmark of libheinsen on one MI355X.
+
+A step is one pass of the whole hot path (one heinsen_scan call: load + encode, fused scan, carry,
+decode + store) over one batch of synthetic input that is already resident in HBM.  The headline
+workload is the linear-RNN-shaped batch [B=8, n=4096, D=1024] float32 (configuration 2); the other
+batched / long workloads are timed as well and reported under "other_workloads".
+
+Prints ONE JSON line: recurrence elements per second, the HBM roofline of the dominant (only) kernel
+measured with HIP events on the launch stream, and the CPU oracle timed on the host cores.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0  # MI355X published HBM3E bandwidth
+
+# HBM bytes per launch measured with rocprofv3 --pmc (FETCH_SIZE, WRITE_SIZE), scaled by the factor a
+# plain copy kernel of known size gives; see profiles/.  None until measured for a workload.
+MEASURED_TRAFFIC_BYTES = {}
+
+
+def device_inputs(cfg, torch, distinct=2):
+    """Full-size device tensors for `cfg`: `distinct` generated batch items, repeated to B items.
+
+    Generating every batch item on the host would take minutes for the 5e8-element workloads; the
+    repeated items have the same distributions and the kernels do not depend on the values."""
+    import numpy as np
+
+    from paper_2311_06281_amd import workloads
+
+    k = min(distinct, cfg.B)
+    batch = workloads.generate(cfg, 0, k)
+    reps = (cfg.B + k - 1) // k
+
+    def up(arr, dtype=None):
+        t = torch.from_numpy(arr).cuda()
+        t = t.repeat((reps,) + (1,) * (t.dim() - 1))[: cfg.B].contiguous()
+        return t
+
+    if cfg.bf16:
+        a = up(batch.a_bits.view(np.int16))
+        b = up(batch.b_bits.view(np.int16))
+    else:
+        a = up(batch.a)
+        b = up(batch.b)
+    if cfg.x0_scalar:
+        x0 = torch.from_numpy(batch.x0).cuda()
+    else:
+        x0 = torch.from_numpy(batch.x0).cuda().reshape(k, cfg.D).repeat(reps, 1)[: cfg.B].contiguous().reshape(-1)
+    out = torch.empty(a.shape, dtype=torch.float32, device="cuda")
+    return a, b, x0, out
+
+
+def time_workload(cfg, torch, hb, steps, warmup):
+    """Returns (wall ms per step, mean kernel ms from HIP events on the launch stream)."""
+    a, b, x0, out = device_inputs(cfg, torch)
+    layout = hb.LAYOUTS[cfg.layout]
+    flags = hb.flags_from_names(cfg.flags)
+    stream = torch.cuda.current_stream()
+
+    def step():
+        hb.heinsen_scan(a, b, x0, out, cfg.B, cfg.D, cfg.n, layout, flags, stream)
+
+    for _ in range(warmup):
+        step()
+    torch.cuda.synchronize()
+    starts = [torch.cuda.Event(enable_timing=True) for _ in range(steps)]
+    ends = [torch.cuda.Event(enable_timing=True) for _ in range(steps)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(steps):
+        starts[i].record(stream)
+        step()
+        ends[i].record(stream)
+    torch.cuda.synchronize()
+    wall_ms = (time.perf_counter() - t0) * 1e3 / steps
+    kern = sorted(s.elapsed_time(e) for s, e in zip(starts, ends))
+    kern_ms = sum(kern) / len(kern)
+    del a, b, x0, out
+    torch.cuda.empty_cache()
+    return wall_ms, kern_ms, kern[len(kern) // 2], kern[0]
+
+
+def cpu_baseline(cfg):
+    """The CPU oracle as it stands, on the host cores, on the same workload (bounded sample)."""
+    import oracle
+    from paper_2311_06281_amd import workloads
+
+    nb = min(cfg.B, 2)
+    batch = workloads.generate(cfg, 0, nb)
+    layout = oracle.LAYOUT_BND if cfg.layout == "BND" else oracle.LAYOUT_BDN
+    fn = oracle.sequential_log if cfg.log_domain else oracle.sequential
+    elements = nb * cfg.D * cfg.n
+    cores = max(1, min(oracle.max_threads(), os.cpu_count() or 1))
+    fn(batch.a, batch.b, batch.x0, layout=layout, threads=cores)  # warm the pages
+    best = {}
+    for threads in (1, cores):
+        reps, t_best, t_total = 0, float("inf"), 0.0
+        while reps < 3 or (t_total < 5.0 and reps < 50):
+            t0 = time.perf_counter()
+            fn(batch.a, batch.b, batch.x0, layout=layout, threads=threads)
+            dt = time.perf_counter() - t0
+            t_best = min(t_best, dt)
+            t_total += dt
+            reps += 1
+        best[threads] = elements / t_best
+    return {"value": best[cores], "unit": "elements/s", "cores": cores, "kind": "oracle",
+            "sample": f"float64 sequential recurrence on {nb} of {cfg.B} batch items of the same workload "
+                      f"({elements} elements), best of repeated runs, channels split over {cores} threads",
+            "single_thread_value": best[1]}
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=30)   # the paper's protocol: mean of 30 runs (Fig. 1)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", type=int, default=2, help="benchmark configuration 1..5 (default 2)")
+    ap.add_argument("--no-others", action="store_true", help="time only the headline workload")
+    ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU (no sharding, no collectives); use --gpus 1", file=sys.stderr)
+        return 2
+
+    import torch
+
+    from paper_2311_06281_amd import binding as hb
+    from paper_2311_06281_amd import workloads
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        return 3
+    hb.load()  # no fallback: raises if the HIP library is missing
+    torch.cuda.set_device(0)
+
+    cfg = workloads.CONFIGS[args.workload]
+    wall_ms, kern_ms, kern_med, kern_min = time_workload(cfg, torch, hb, args.steps, args.warmup)
+    E = cfg.elements
+    alg_bytes = cfg.bytes_per_element * E
+    achieved = alg_bytes / (kern_ms * 1e-3) / 1e9
+    kernel = hb.heinsen_kernel_name(cfg.B, cfg.D, cfg.n, hb.LAYOUTS[cfg.layout], hb.flags_from_names(cfg.flags))
+    result = {
+        "metric": "recurrence elements/sec",
+        "value": E / (wall_ms * 1e-3),
+        "unit": "elements/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": wall_ms,
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "f32",
+        "data": "synthetic",
+        "config": {"workload": f"cfg{cfg.index}: {cfg.name}", "B": cfg.B, "D": cfg.D, "n": cfg.n,
+                   "layout": cfg.layout, "flags": list(cfg.flags), "bytes_per_element": cfg.bytes_per_element},
+        "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": achieved / HBM_PEAK_GBS, "traffic": MEASURED_TRAFFIC_BYTES.get(cfg.index),
+                     "kernel": kernel, "kernel_ms_mean": kern_ms, "kernel_ms_median": kern_med,
+                     "kernel_ms_min": kern_min, "algorithmic_bytes": alg_bytes},
+    }
+    if not args.no_others:
+        others = []
+        for idx in (1, 3, 4, 5):
+            if idx == cfg.index:
+                continue
+            c = workloads.CONFIGS[idx]
+            w_ms, k_ms, k_med, k_min = time_workload(c, torch, hb, max(5, min(args.steps, 10)), 2)
+            gbs = c.bytes_per_element * c.elements / (k_ms * 1e-3) / 1e9
+            others.append({"workload": f"cfg{idx}: {c.name}", "elements_per_s": c.elements / (w_ms * 1e-3),
+                           "ms_per_step": w_ms, "kernel_ms_mean": k_ms, "kernel_ms_min": k_min,
+                           "achieved_GBps": gbs, "frac_of_hbm_peak": gbs / HBM_PEAK_GBS,
+                           "kernel": hb.heinsen_kernel_name(c.B, c.D, c.n, hb.LAYOUTS[c.layout],
+                                                            hb.flags_from_names(c.flags))})
+        result["other_workloads"] = others
+    if not args.no_cpu:
+        result["cpu_baseline"] = cpu_baseline(cfg)
+    print(json.dumps(result))
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())
