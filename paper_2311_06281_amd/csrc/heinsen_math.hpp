@@ -18,6 +18,9 @@
 
 namespace hs {
 
+// Sign words: bit 31 is the sign (1 = negative); the other 31 bits are undefined and every consumer
+// either ignores them or masks them.  This lets the raw bits of an input float serve as its sign word.
+
 constexpr float kLog2e = 1.44269504088896340736f;
 constexpr float kLn2 = 0.69314718055994530942f;
 constexpr uint32_t kSignBit = 0x80000000u;
@@ -38,7 +41,7 @@ __device__ __forceinline__ void slae(float p, uint32_t sp, float q, uint32_t sq,
     t = (p == q) ? 0.0f : t;
     float e = exp2_hw(-fabsf(t));
     if (SIGNED) {
-        e = u2f(f2u(e) ^ (sp ^ sq));
+        e = u2f(f2u(e) ^ ((sp ^ sq) & kSignBit));
         sr = (t >= 0.0f) ? sp : sq;
     } else {
         sr = 0;
@@ -46,31 +49,10 @@ __device__ __forceinline__ void slae(float p, uint32_t sp, float q, uint32_t sq,
     r = m + log2_hw(1.0f + e);
 }
 
-// sp 2^p + sq 2^q as a float32 number (Eq. (3): the exponential of Eq. (1), with the logarithm of the
-// last addition never formed).  2^m is applied as two factors 2^(m/2) so that a sum that fits
-// float32 is not lost to an intermediate overflow of its larger term.
-template <bool SIGNED>
-__device__ __forceinline__ float lin_sum(float p, uint32_t sp, float q, uint32_t sq)
-{
-    float m = fmaxf(p, q);
-    float t = p - q;
-    t = (p == q) ? 0.0f : t;
-    float e = exp2_hw(-fabsf(t));
-    uint32_t sr = 0;
-    if (SIGNED) {
-        e = u2f(f2u(e) ^ (sp ^ sq));
-        sr = (t >= 0.0f) ? sp : sq;
-    }
-    float u = 1.0f + e;
-    float h = exp2_hw(0.5f * m);
-    float x = (u * h) * h;
-    return SIGNED ? u2f(f2u(x) ^ sr) : x;
-}
-
 // One segment summary.
 struct Seg {
     float A, M;
-    uint32_t sA, sM; // 0 or kSignBit
+    uint32_t sA, sM; // sign words
 };
 
 __device__ __forceinline__ Seg seg_identity() { return Seg{0.0f, -INFINITY, 0u, 0u}; }
@@ -114,24 +96,57 @@ __device__ __forceinline__ void encode(float v, float &l, uint32_t &s)
         s = 0;
     } else if (SIGNED) {
         l = log2_hw(fabsf(v));
-        s = f2u(v) & kSignBit;
+        s = f2u(v);
     } else {
         l = log2_hw(v);
         s = 0;
     }
 }
 
-// Output value of an element whose segment-from-lane-start summary is g and whose lane started from x.
+// ---- per-element record between the scan and the emit ------------------------------------------------
+//
+// After the serial scan a lane holds, for each of its elements k, the summary (A_k, M_k) of the lane's
+// steps up to k.  Once the state x_s = (+-)2^lx at the lane's first step is known, the element is
+//     x_k = (+-)2^(lx + A_k) + (+-)2^(M_k)                    (Eq. (3) with x_0 := x_s)
+// or, for a log output, log x_k = slae(lx + A_k, M_k) (Eq. (1)).  Two floats are kept per element:
+//   linear output: r0 = A_k, r1 = (+-)2^(M_k) already exponentiated with its sign in the sign bit; the
+//                  sign of the 2^A factor goes to bit k of the lane's sign word `sw`;
+//   log output:    r0 = A_k, r1 = M_k (positive domain, no signs).
+// The first term is formed in the log domain so that a large local product times a small state (or
+// the reverse) does not overflow or flush on the way.
 template <bool SIGNED, bool LOG_OUT>
-__device__ __forceinline__ float emit(const State &x, float A, uint32_t sA, float M, uint32_t sM)
+__device__ __forceinline__ void stash(const Seg &run, int k, float &r0, float &r1, uint32_t &sw)
+{
+    r0 = run.A;
+    if (LOG_OUT) {
+        r1 = run.M;
+    } else {
+        const float e = exp2_hw(run.M);
+        r1 = SIGNED ? u2f(f2u(e) ^ (run.sM & kSignBit)) : e;
+        if (SIGNED) sw |= (run.sA >> 31) << k;
+    }
+}
+
+// Folds the sign of the lane's start state into the sign word, once per lane.
+template <bool SIGNED>
+__device__ __forceinline__ uint32_t fold_state_sign(uint32_t sw, const State &x)
+{
+    return SIGNED ? (sw ^ (uint32_t)((int32_t)x.s >> 31)) : 0u;
+}
+
+// swx = fold_state_sign(sw, x).
+template <bool SIGNED, bool LOG_OUT>
+__device__ __forceinline__ float emit(const State &x, float r0, float r1, uint32_t swx, int k)
 {
     if (LOG_OUT) {
         float r;
         uint32_t sr;
-        slae<false>(x.lx + A, 0u, M, 0u, r, sr);
+        slae<false>(x.lx + r0, 0u, r1, 0u, r, sr);
         return r * kLn2;
     }
-    return lin_sum<SIGNED>(x.lx + A, SIGNED ? (x.s ^ sA) : 0u, M, sM);
+    float e = exp2_hw(x.lx + r0);
+    if (SIGNED) e = u2f(f2u(e) ^ ((swx << (31 - k)) & kSignBit));
+    return e + r1;
 }
 
 // ---- wave64 cross-lane scan of segment summaries (DPP row shifts + row broadcasts) -----------------
@@ -187,5 +202,22 @@ __device__ __forceinline__ uint32_t readlane_u(uint32_t v, int lane)
 {
     return (uint32_t)__builtin_amdgcn_readlane((int)v, lane);
 }
+
+// ---- publishing carries between workgroups ------------------------------------------------------------
+//
+// Carries travel through global memory as relaxed agent-scope atomics, which are served at the level
+// of the memory hierarchy all compute dies share, so no cache write-back or invalidate is needed
+// (an agent-scope release/acquire fence would write back / invalidate a whole L2 per tile).  What
+// remains is ordering inside the publishing and the consuming wave: payload stores complete before the
+// flag store is issued, and payload loads are issued after the flag was seen.
+__device__ __forceinline__ void order_release() { __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup"); }
+__device__ __forceinline__ void order_acquire() { __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup"); }
+
+__device__ __forceinline__ void pub_f(float *p, float v) { __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); }
+__device__ __forceinline__ void pub_u(uint32_t *p, uint32_t v) { __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); }
+__device__ __forceinline__ void pub_d(double *p, double v) { __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); }
+__device__ __forceinline__ float get_f(const float *p) { return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); }
+__device__ __forceinline__ uint32_t get_u(const uint32_t *p) { return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); }
+__device__ __forceinline__ double get_d(const double *p) { return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); }
 
 } // namespace hs

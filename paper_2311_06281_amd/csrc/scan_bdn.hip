@@ -64,13 +64,13 @@ __device__ __forceinline__ void lane_load(const InT *arow, const InT *brow, int6
     }
 }
 
-// Encodes and scans the lane's elements serially.  On return Av[k], Mv[k] and bit k of sAw, sMw hold
-// the summary of the lane's steps 0..k; the summary of all ITEMS steps is returned.
-template <bool SIGNED, bool LOG_IN, int ITEMS>
-__device__ __forceinline__ Seg lane_scan(float (&Av)[ITEMS], float (&Mv)[ITEMS], uint32_t &sAw, uint32_t &sMw)
+// Encodes and scans the lane's elements serially.  On return Av[k], Mv[k] and bit k of sw hold the
+// per-element records (see stash); the summary of all ITEMS steps is returned.
+template <bool SIGNED, bool LOG_IN, bool LOG_OUT, int ITEMS>
+__device__ __forceinline__ Seg lane_scan(float (&Av)[ITEMS], float (&Mv)[ITEMS], uint32_t &sw)
 {
     static_assert(ITEMS <= 32, "sign bits are kept in one word");
-    sAw = sMw = 0u;
+    sw = 0u;
     Seg run;
 #pragma unroll
     for (int k = 0; k < ITEMS; ++k) {
@@ -86,12 +86,7 @@ __device__ __forceinline__ Seg lane_scan(float (&Av)[ITEMS], float (&Mv)[ITEMS],
             run.A += la;
             if (SIGNED) run.sA ^= sa;
         }
-        Av[k] = run.A;
-        Mv[k] = run.M;
-        if (SIGNED) {
-            sAw |= (run.sA >> 31) << k;
-            sMw |= (run.sM >> 31) << k;
-        }
+        stash<SIGNED, LOG_OUT>(run, k, Av[k], Mv[k], sw);
     }
     return run;
 }
@@ -99,16 +94,12 @@ __device__ __forceinline__ Seg lane_scan(float (&Av)[ITEMS], float (&Mv)[ITEMS],
 // Emits the lane's elements given the state at the lane's first step.
 template <bool SIGNED, bool LOG_OUT, int ITEMS, bool VECIO>
 __device__ __forceinline__ void lane_emit(float *orow, int64_t start, int64_t n, const State &st,
-                                          const float (&Av)[ITEMS], const float (&Mv)[ITEMS], uint32_t sAw,
-                                          uint32_t sMw)
+                                          const float (&Av)[ITEMS], const float (&Mv)[ITEMS], uint32_t sw)
 {
     float o[ITEMS];
+    const uint32_t swx = fold_state_sign<SIGNED>(sw, st);
 #pragma unroll
-    for (int k = 0; k < ITEMS; ++k) {
-        const uint32_t sA = SIGNED ? ((sAw >> k) << 31) : 0u;
-        const uint32_t sM = SIGNED ? ((sMw >> k) << 31) : 0u;
-        o[k] = emit<SIGNED, LOG_OUT>(st, Av[k], sA, Mv[k], sM);
-    }
+    for (int k = 0; k < ITEMS; ++k) o[k] = emit<SIGNED, LOG_OUT>(st, Av[k], Mv[k], swx, k);
     if (VECIO) {
         typedef float vec_t __attribute__((ext_vector_type(4)));
 #pragma unroll
@@ -151,15 +142,15 @@ __global__ __launch_bounds__(256) void heinsen_scan_rows_wave(RowsParams p)
     const int64_t start = (int64_t)lane * ITEMS;
 
     float Av[ITEMS], Mv[ITEMS];
-    uint32_t sAw, sMw;
+    uint32_t sw;
     lane_load<LOG_IN, InT, ITEMS, VECIO>(arow, brow, start, p.n, Av, Mv);
-    Seg mine = lane_scan<SIGNED, LOG_IN, ITEMS>(Av, Mv, sAw, sMw);
+    Seg mine = lane_scan<SIGNED, LOG_IN, LOG_OUT, ITEMS>(Av, Mv, sw);
     Seg excl = wave_shift_up<SIGNED>(wave_inclusive_scan<SIGNED>(mine));
 
     State st;
     encode<SIGNED, LOG_IN>(p.x0[p.x0_stride ? row : 0], st.lx, st.s);
     st = seg_apply<SIGNED>(st, excl);
-    lane_emit<SIGNED, LOG_OUT, ITEMS, VECIO>(p.out + row * p.n, start, p.n, st, Av, Mv, sAw, sMw);
+    lane_emit<SIGNED, LOG_OUT, ITEMS, VECIO>(p.out + row * p.n, start, p.n, st, Av, Mv, sw);
 }
 
 // ---- tiles with a chained carry ------------------------------------------------------------------------
@@ -211,7 +202,7 @@ __device__ __forceinline__ State64 seg_apply64(const State64 &x, const Seg &g)
     State64 r;
     r.s = 0u;
     if (SIGNED) {
-        e = u2f(f2u(e) ^ (sp ^ g.sM));
+        e = u2f(f2u(e) ^ ((sp ^ g.sM) & kSignBit));
         r.s = (t >= 0.0f) ? sp : g.sM;
     }
     r.lx = m + (double)log2_hw(1.0f + e);
@@ -246,15 +237,15 @@ __global__ __launch_bounds__(kTileWaves * 64) void heinsen_scan_tiles(TileParams
     const int64_t start = (int64_t)c * kTile + (int64_t)threadIdx.x * ITEMS;
 
     float Av[ITEMS], Mv[ITEMS];
-    uint32_t sAw, sMw;
+    uint32_t sw;
     lane_load<LOG_IN, InT, ITEMS, VECIO>(arow, brow, start, p.n, Av, Mv);
-    Seg mine = lane_scan<SIGNED, LOG_IN, ITEMS>(Av, Mv, sAw, sMw);
+    Seg mine = lane_scan<SIGNED, LOG_IN, LOG_OUT, ITEMS>(Av, Mv, sw);
     Seg incl = wave_inclusive_scan<SIGNED>(mine);
     Seg lane_excl = wave_shift_up<SIGNED>(incl);
     if (lane == 63) {
         lds_A[w] = incl.A;
         lds_M[w] = incl.M;
-        lds_S[w] = (incl.sA >> 31) | (incl.sM >> 30);
+        lds_S[w] = (incl.sA >> 31) | ((incl.sM >> 31) << 1);
     }
     __syncthreads();
 
@@ -267,7 +258,7 @@ __global__ __launch_bounds__(kTileWaves * 64) void heinsen_scan_tiles(TileParams
         h.A = lds_A[j];
         h.M = lds_M[j];
         h.sA = SIGNED ? (lds_S[j] << 31) : 0u;
-        h.sM = SIGNED ? ((lds_S[j] << 30) & kSignBit) : 0u;
+        h.sM = SIGNED ? (lds_S[j] << 30) : 0u;
         total = (j == 0) ? h : seg_combine<SIGNED>(total, h);
         if (j + 1 == w) wave_excl = total;
     }
@@ -284,11 +275,11 @@ __global__ __launch_bounds__(kTileWaves * 64) void heinsen_scan_tiles(TileParams
             const bool more = c + 1 < p.tpr;
             if (more && r < kGroupK - 1) {
                 if (lane == 0) {
-                    p.agg_A[tile] = total.A;
-                    p.agg_M[tile] = total.M;
-                    p.agg_S[tile] = (total.sA >> 31) | (total.sM >> 30);
+                    pub_f(&p.agg_A[tile], total.A);
+                    pub_f(&p.agg_M[tile], total.M);
+                    pub_u(&p.agg_S[tile], (total.sA >> 31) | ((total.sM >> 31) << 1));
                 }
-                __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent");
+                order_release();
                 if (lane == 0) __hip_atomic_store(&p.agg_flag[tile], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             }
             // lane i folds the summaries of tiles first + i*kPerLane .. + kPerLane - 1 that precede c
@@ -306,7 +297,7 @@ __global__ __launch_bounds__(kTileWaves * 64) void heinsen_scan_tiles(TileParams
                     while (__hip_atomic_load(&p.st_flag[row * p.gpr + g], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == 0u)
                         __builtin_amdgcn_s_sleep(2);
                 }
-                __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
+                order_acquire();
             }
             Seg part = seg_identity();
 #pragma unroll
@@ -314,11 +305,11 @@ __global__ __launch_bounds__(kTileWaves * 64) void heinsen_scan_tiles(TileParams
                 const uint32_t rr = (uint32_t)lane * kPerLane + j;
                 Seg h = seg_identity();
                 if (rr < r) {
-                    h.A = p.agg_A[first + rr];
-                    h.M = p.agg_M[first + rr];
-                    const uint32_t s = SIGNED ? p.agg_S[first + rr] : 0u;
+                    h.A = get_f(&p.agg_A[first + rr]);
+                    h.M = get_f(&p.agg_M[first + rr]);
+                    const uint32_t s = SIGNED ? get_u(&p.agg_S[first + rr]) : 0u;
                     h.sA = s << 31;
-                    h.sM = (s << 30) & kSignBit;
+                    h.sM = s << 30;
                 }
                 part = (j == 0) ? h : seg_combine<SIGNED>(part, h);
             }
@@ -333,17 +324,17 @@ __global__ __launch_bounds__(kTileWaves * 64) void heinsen_scan_tiles(TileParams
                 encode<SIGNED, LOG_IN>(p.x0[p.x0_stride ? row : 0], lx, st.s);
                 st.lx = (double)lx;
             } else {
-                st.lx = p.st_L[row * p.gpr + g];
-                st.s = SIGNED ? p.st_S[row * p.gpr + g] : 0u;
+                st.lx = get_d(&p.st_L[row * p.gpr + g]);
+                st.s = SIGNED ? get_u(&p.st_S[row * p.gpr + g]) : 0u;
             }
             if (r > 0) st = seg_apply64<SIGNED>(st, fold);
             if (more && r == kGroupK - 1) {
                 State64 nx = seg_apply64<SIGNED>(st, total);
                 if (lane == 0) {
-                    p.st_L[row * p.gpr + g + 1] = nx.lx;
-                    p.st_S[row * p.gpr + g + 1] = nx.s;
+                    pub_d(&p.st_L[row * p.gpr + g + 1], nx.lx);
+                    pub_u(&p.st_S[row * p.gpr + g + 1], nx.s);
                 }
-                __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent");
+                order_release();
                 if (lane == 0)
                     __hip_atomic_store(&p.st_flag[row * p.gpr + g + 1], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             }
@@ -359,14 +350,14 @@ __global__ __launch_bounds__(kTileWaves * 64) void heinsen_scan_tiles(TileParams
     st.lx = lds_startL;
     st.s = lds_startS;
     st = seg_apply<SIGNED>(st, seg_combine<SIGNED>(wave_excl, lane_excl));
-    lane_emit<SIGNED, LOG_OUT, ITEMS, VECIO>(p.out + row * p.n, start, p.n, st, Av, Mv, sAw, sMw);
+    lane_emit<SIGNED, LOG_OUT, ITEMS, VECIO>(p.out + row * p.n, start, p.n, st, Av, Mv, sw);
 
     if (MULTI) {
         // the last workgroup to finish restores the zeros in the flag region
         __syncthreads();
         if (threadIdx.x == 0) {
-            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent");
-            uint32_t prev = __hip_atomic_fetch_add(&p.counters[1], 1u, __ATOMIC_ACQ_REL, __HIP_MEMORY_SCOPE_AGENT);
+            order_release();
+            uint32_t prev = __hip_atomic_fetch_add(&p.counters[1], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             s_last = (prev == p.ntiles - 1u) ? 1u : 0u;
         }
         __syncthreads();

@@ -13,6 +13,7 @@
 // arithmetic is in heinsen_math.hpp.
 #include "heinsen_internal.hpp"
 #include "heinsen_math.hpp"
+#include <cstdlib>
 
 namespace hs {
 namespace {
@@ -66,18 +67,18 @@ __device__ __forceinline__ void store_vec(float *p, const float (&v)[VEC])
 }
 __device__ __forceinline__ void store_vec(float *p, const float (&v)[1]) { *p = v[0]; }
 
-__device__ __forceinline__ uint32_t pack_signs(const Seg &g) { return (g.sA >> 31) | (g.sM >> 30); }
+__device__ __forceinline__ uint32_t pack_signs(const Seg &g) { return (g.sA >> 31) | ((g.sM >> 31) << 1); }
 __device__ __forceinline__ void unpack_signs(uint32_t s, Seg &g)
 {
     g.sA = s << 31;
-    g.sM = (s << 30) & kSignBit;
+    g.sM = s << 30;
 }
 
-template <bool SIGNED, bool LOG_IN, bool LOG_OUT, typename InT, int VEC, int T, int NW>
-__global__ __launch_bounds__(NW * 64) void heinsen_scan_bnd(BndParams p)
+template <bool SIGNED, bool LOG_IN, bool LOG_OUT, typename InT, int VEC, int T, int NW, int MINW = 1>
+__global__ __launch_bounds__(NW * 64, MINW) void heinsen_scan_bnd(BndParams p)
 {
     constexpr int CH = 64 * VEC;
-    constexpr int NBITW = (T * VEC + 31) / 32;
+    static_assert(T <= 32, "one sign word per channel");
     __shared__ uint32_t s_tile;
     __shared__ uint32_t s_last;
     __shared__ float lds_A[NW][CH];
@@ -132,11 +133,11 @@ __global__ __launch_bounds__(NW * 64) void heinsen_scan_bnd(BndParams p)
         }
     }
 
-    // ---- encode + serial scan in each lane; Av/Mv become the running (A_k, M_k) ------------------
-    uint32_t sAw[NBITW], sMw[NBITW];
-#pragma unroll
-    for (int i = 0; i < NBITW; ++i) sAw[i] = sMw[i] = 0u;
+    // ---- encode + serial scan in each lane; Av/Mv become the per-element records (see stash) --------
+    uint32_t sw[VEC];
     Seg run[VEC];
+#pragma unroll
+    for (int v = 0; v < VEC; ++v) sw[v] = 0u;
 #pragma unroll
     for (int k = 0; k < T; ++k) {
 #pragma unroll
@@ -153,13 +154,7 @@ __global__ __launch_bounds__(NW * 64) void heinsen_scan_bnd(BndParams p)
                 run[v].A += la;
                 if (SIGNED) run[v].sA ^= sa;
             }
-            Av[k][v] = run[v].A;
-            Mv[k][v] = run[v].M;
-            if (SIGNED) {
-                const int bit = k * VEC + v;
-                sAw[bit / 32] |= (run[v].sA >> 31) << (bit % 32);
-                sMw[bit / 32] |= (run[v].sM >> 31) << (bit % 32);
-            }
+            stash<SIGNED, LOG_OUT>(run[v], k, Av[k][v], Mv[k][v], sw[v]);
         }
     }
 
@@ -205,11 +200,11 @@ __global__ __launch_bounds__(NW * 64) void heinsen_scan_bnd(BndParams p)
         if (more && r < kGroup - 1) {
 #pragma unroll
             for (int v = 0; v < VEC; ++v) {
-                p.agg_A[my + v] = pre[v].A;
-                p.agg_M[my + v] = pre[v].M;
-                if (SIGNED) p.agg_S[my + v] = pack_signs(pre[v]);
+                pub_f(&p.agg_A[my + v], pre[v].A);
+                pub_f(&p.agg_M[my + v], pre[v].M);
+                if (SIGNED) pub_u(&p.agg_S[my + v], pack_signs(pre[v]));
             }
-            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent");
+            order_release();
             if (lane == 0) __hip_atomic_store(&p.agg_flag[tile], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         }
 
@@ -224,7 +219,7 @@ __global__ __launch_bounds__(NW * 64) void heinsen_scan_bnd(BndParams p)
                 while (__hip_atomic_load(fp, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == 0u)
                     __builtin_amdgcn_s_sleep(2);
             }
-            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
+            order_acquire();
         }
 
         State st[VEC];
@@ -239,8 +234,8 @@ __global__ __launch_bounds__(NW * 64) void heinsen_scan_bnd(BndParams p)
             const size_t si = ((size_t)g * p.ncols + col) * CH + (size_t)lane * VEC;
 #pragma unroll
             for (int v = 0; v < VEC; ++v) {
-                st[v].lx = p.st_L[si + v];
-                st[v].s = SIGNED ? p.st_S[si + v] : 0u;
+                st[v].lx = get_f(&p.st_L[si + v]);
+                st[v].s = SIGNED ? get_u(&p.st_S[si + v]) : 0u;
             }
         }
         if (r > 0) {
@@ -253,9 +248,9 @@ __global__ __launch_bounds__(NW * 64) void heinsen_scan_bnd(BndParams p)
                     const size_t ti = ((size_t)(g * kGroup + j) * p.ncols + col) * CH + (size_t)lane * VEC;
 #pragma unroll
                     for (int v = 0; v < VEC; ++v) {
-                        fA[j][v] = p.agg_A[ti + v];
-                        fM[j][v] = p.agg_M[ti + v];
-                        fS[j][v] = SIGNED ? p.agg_S[ti + v] : 0u;
+                        fA[j][v] = get_f(&p.agg_A[ti + v]);
+                        fM[j][v] = get_f(&p.agg_M[ti + v]);
+                        fS[j][v] = SIGNED ? get_u(&p.agg_S[ti + v]) : 0u;
                     }
                 }
             }
@@ -285,10 +280,10 @@ __global__ __launch_bounds__(NW * 64) void heinsen_scan_bnd(BndParams p)
 #pragma unroll
             for (int v = 0; v < VEC; ++v) {
                 State nx = seg_apply<SIGNED>(st[v], pre[v]);
-                p.st_L[si + v] = nx.lx;
-                if (SIGNED) p.st_S[si + v] = nx.s;
+                pub_f(&p.st_L[si + v], nx.lx);
+                if (SIGNED) pub_u(&p.st_S[si + v], nx.s);
             }
-            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent");
+            order_release();
             if (lane == 0)
                 __hip_atomic_store(&p.st_flag[(size_t)(g + 1) * p.ncols + col], 1u, __ATOMIC_RELAXED,
                                    __HIP_MEMORY_SCOPE_AGENT);
@@ -306,24 +301,22 @@ __global__ __launch_bounds__(NW * 64) void heinsen_scan_bnd(BndParams p)
     }
     float *op = p.out + base;
     const bool full = chan_ok && t0 + T <= p.n;
+    uint32_t swx[VEC];
+#pragma unroll
+    for (int v = 0; v < VEC; ++v) swx[v] = fold_state_sign<SIGNED>(sw[v], st[v]);
 #pragma unroll
     for (int k = 0; k < T; ++k) {
         float o[VEC];
 #pragma unroll
-        for (int v = 0; v < VEC; ++v) {
-            const int bit = k * VEC + v;
-            const uint32_t sA = SIGNED ? ((sAw[bit / 32] >> (bit % 32)) << 31) : 0u;
-            const uint32_t sM = SIGNED ? ((sMw[bit / 32] >> (bit % 32)) << 31) : 0u;
-            o[v] = emit<SIGNED, LOG_OUT>(st[v], Av[k][v], sA, Mv[k][v], sM);
-        }
+        for (int v = 0; v < VEC; ++v) o[v] = emit<SIGNED, LOG_OUT>(st[v], Av[k][v], Mv[k][v], swx[v], k);
         if (full || (chan_ok && t0 + k < p.n)) store_vec(op + (int64_t)k * p.D, o);
     }
 
     // ---- the last workgroup to finish restores the zeros in the flag region ------------------------
     __syncthreads(); // wave 0's polls are over before this workgroup reports completion
     if (threadIdx.x == 0) {
-        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent");
-        uint32_t prev = __hip_atomic_fetch_add(&p.counters[1], 1u, __ATOMIC_ACQ_REL, __HIP_MEMORY_SCOPE_AGENT);
+        order_release();
+        uint32_t prev = __hip_atomic_fetch_add(&p.counters[1], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         s_last = (prev == p.ntiles - 1u) ? 1u : 0u;
     }
     __syncthreads();
@@ -339,7 +332,7 @@ __global__ __launch_bounds__(NW * 64) void heinsen_scan_bnd(BndParams p)
 // ---- host side ------------------------------------------------------------------------------------
 
 struct BndPlan {
-    int vec, T, NW, CH;
+    int vec, T, NW, CH, variant;
     int cols_per_b, ncols, nchunks, ngroups;
     uint32_t ntiles;
     size_t off_agg_flag, off_st_flag, flag_bytes;                      // inside the flag buffer
@@ -355,6 +348,18 @@ BndPlan make_plan(const ScanCall &c)
     if (c.D % 2 == 0 && aligned(c.a, 2 * in_sz) && aligned(c.b, 2 * in_sz) && aligned(c.out, 8)) pl.vec = 2;
     pl.T = 16;
     pl.NW = 8;
+    pl.variant = 0;
+    if (const char *ev = getenv("HEINSEN_BND_VARIANT")) {
+        pl.variant = atoi(ev);
+        static const int tab[][3] = {{0, 0, 0}, {2, 16, 8}, {2, 16, 4}, {2, 8, 8}, {4, 8, 8}, {4, 8, 4}, {1, 32, 4}, {2, 32, 4}, {1, 16, 8}, {4, 4, 16}, {2, 8, 16}};
+        if (pl.variant >= 1 && pl.variant <= 10 && c.is_signed && !c.bf16 && c.D % 4 == 0) {
+            pl.vec = tab[pl.variant][0];
+            pl.T = tab[pl.variant][1];
+            pl.NW = tab[pl.variant][2];
+        } else {
+            pl.variant = 0;
+        }
+    }
     pl.CH = 64 * pl.vec;
     pl.cols_per_b = (int)ceil_div(c.D, pl.CH);
     pl.ncols = (int)(c.B * pl.cols_per_b);
@@ -404,6 +409,24 @@ hipError_t launch_mode(const ScanCall &c, const BndPlan &pl, char *flags, char *
     p.st_L = reinterpret_cast<float *>(data + pl.off_st_L);
     p.st_S = reinterpret_cast<uint32_t *>(data + pl.off_st_S);
     dim3 grid(pl.ntiles), block(pl.NW * 64);
+    if constexpr (SIGNED && sizeof(InT) == 4) {
+#define HS_VAR(ID, V, T_, NW_, MW)                                                                                 \
+    if (pl.variant == ID) {                                                                                        \
+        hipLaunchKernelGGL((heinsen_scan_bnd<SIGNED, LOG_IN, LOG_OUT, InT, V, T_, NW_, MW>), grid, block, 0, c.stream, p); \
+        return hipGetLastError();                                                                                  \
+    }
+        HS_VAR(1, 2, 16, 8, 2)
+        HS_VAR(2, 2, 16, 4, 2)
+        HS_VAR(3, 2, 8, 8, 2)
+        HS_VAR(4, 4, 8, 8, 2)
+        HS_VAR(5, 4, 8, 4, 2)
+        HS_VAR(6, 1, 32, 4, 2)
+        HS_VAR(7, 2, 32, 4, 1)
+        HS_VAR(8, 1, 16, 8, 2)
+        HS_VAR(9, 4, 4, 16, 4)
+        HS_VAR(10, 2, 8, 16, 4)
+#undef HS_VAR
+    }
     if (pl.vec == 2)
         hipLaunchKernelGGL((heinsen_scan_bnd<SIGNED, LOG_IN, LOG_OUT, InT, 2, 16, 8>), grid, block, 0, c.stream, p);
     else
