@@ -124,6 +124,10 @@ __device__ __forceinline__ void stash(const Seg &run, int k, float &r0, float &r
         const float e = exp2_hw(run.M);
         r1 = SIGNED ? u2f(f2u(e) ^ (run.sM & kSignBit)) : e;
         if (SIGNED) sw |= (run.sA >> 31) << k;
+        // Materialise the record here: left alone the optimiser sinks this work to the emit phase and
+        // keeps (A_k, M_k, sign) of every element alive in separate registers until then.
+        asm volatile("" : "+v"(r1));
+        if (SIGNED) asm volatile("" : "+v"(sw));
     }
 }
 
@@ -208,9 +212,16 @@ __device__ __forceinline__ uint32_t readlane_u(uint32_t v, int lane)
 // Carries travel through global memory as relaxed agent-scope atomics, which are served at the level
 // of the memory hierarchy all compute dies share, so no cache write-back or invalidate is needed
 // (an agent-scope release/acquire fence would write back / invalidate a whole L2 per tile).  What
-// remains is ordering inside the publishing and the consuming wave: payload stores complete before the
-// flag store is issued, and payload loads are issued after the flag was seen.
-__device__ __forceinline__ void order_release() { __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup"); }
+// remains is ordering inside the publishing and the consuming wave.  Publisher: every payload store
+// must have been acknowledged before the flag store is issued -- stores of one wave to different
+// addresses may complete in any order, and a workgroup-scope fence does not wait for them, hence
+// the explicit s_waitcnt.  Consumer: payload loads are issued only after the flag value has come
+// back (the branch on it is a real dependency); the fence keeps the compiler from moving them up.
+__device__ __forceinline__ void order_release()
+{
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+}
 __device__ __forceinline__ void order_acquire() { __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup"); }
 
 __device__ __forceinline__ void pub_f(float *p, float v) { __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); }

@@ -171,8 +171,7 @@ struct TileParams {
     uint32_t tpr;       // tiles per row
     uint32_t gpr;       // groups per row
     uint32_t ntiles;    // rows * tpr
-    uint32_t nflags;    // words in the flag region after the counters
-    uint32_t *counters; // [0] ticket, [1] done
+    uint32_t *counters; // [0] ticket
     uint32_t *agg_flag; // [ntiles]
     uint32_t *st_flag;  // [rows * gpr]
     float *agg_A;       // [ntiles]
@@ -214,7 +213,7 @@ __global__ __launch_bounds__(kTileWaves * 64) void heinsen_scan_tiles(TileParams
 {
     constexpr int NW = kTileWaves;
     constexpr int ITEMS = kTileItems;
-    __shared__ uint32_t s_tile, s_last;
+    __shared__ uint32_t s_tile;
     __shared__ float lds_A[NW], lds_M[NW];
     __shared__ uint32_t lds_S[NW];
     __shared__ float lds_startL;
@@ -226,9 +225,14 @@ __global__ __launch_bounds__(kTileWaves * 64) void heinsen_scan_tiles(TileParams
     uint32_t tile = blockIdx.x;
     if (MULTI) {
         // tickets: a tile only ever waits for tiles with smaller tickets, which are already running
-        if (threadIdx.x == 0) s_tile = atomicAdd(&p.counters[0], 1u);
+        // whoever draws the last ticket puts the counter back to zero for the next launch
+        if (threadIdx.x == 0) {
+            const uint32_t tk = atomicAdd(&p.counters[0], 1u);
+            if (tk == p.ntiles - 1u) pub_u(&p.counters[0], 0u);
+            s_tile = tk;
+        }
         __syncthreads();
-        tile = s_tile;
+        tile = __builtin_amdgcn_readfirstlane(s_tile);
     }
     const int64_t row = tile / p.tpr;
     const uint32_t c = tile % p.tpr;
@@ -280,7 +284,10 @@ __global__ __launch_bounds__(kTileWaves * 64) void heinsen_scan_tiles(TileParams
                     pub_u(&p.agg_S[tile], (total.sA >> 31) | ((total.sM >> 31) << 1));
                 }
                 order_release();
-                if (lane == 0) __hip_atomic_store(&p.agg_flag[tile], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                // A flag holds the number of tiles that will still read the record; each reader takes
+                // one off after its read, so the flag is back at zero when the kernel ends.
+                const uint32_t last_in_group = min(g * kGroupK + kGroupK - 1, p.tpr - 1);
+                if (lane == 0) pub_u(&p.agg_flag[tile], last_in_group - c);
             }
             // lane i folds the summaries of tiles first + i*kPerLane .. + kPerLane - 1 that precede c
             const uint32_t first = tile - r; // first tile of the group (same row)
@@ -289,13 +296,13 @@ __global__ __launch_bounds__(kTileWaves * 64) void heinsen_scan_tiles(TileParams
                 for (int j = 0; j < kPerLane; ++j) {
                     const uint32_t rr = (uint32_t)lane * kPerLane + j;
                     if (rr < r) {
-                        while (__hip_atomic_load(&p.agg_flag[first + rr], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == 0u)
-                            __builtin_amdgcn_s_sleep(2);
+                        while (get_u(&p.agg_flag[first + rr]) == 0u) __builtin_amdgcn_s_sleep(2);
+                        (void)__hip_atomic_fetch_sub(&p.agg_flag[first + rr], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
                     }
                 }
                 if (g > 0 && lane == 63) {
-                    while (__hip_atomic_load(&p.st_flag[row * p.gpr + g], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == 0u)
-                        __builtin_amdgcn_s_sleep(2);
+                    while (get_u(&p.st_flag[row * p.gpr + g]) == 0u) __builtin_amdgcn_s_sleep(2);
+                    (void)__hip_atomic_fetch_sub(&p.st_flag[row * p.gpr + g], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
                 }
                 order_acquire();
             }
@@ -335,8 +342,8 @@ __global__ __launch_bounds__(kTileWaves * 64) void heinsen_scan_tiles(TileParams
                     pub_u(&p.st_S[row * p.gpr + g + 1], nx.s);
                 }
                 order_release();
-                if (lane == 0)
-                    __hip_atomic_store(&p.st_flag[row * p.gpr + g + 1], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                const uint32_t next_group_tiles = min((uint32_t)kGroupK, p.tpr - (g + 1) * kGroupK);
+                if (lane == 0) pub_u(&p.st_flag[row * p.gpr + g + 1], next_group_tiles);
             }
         }
         if (lane == 0) {
@@ -352,23 +359,6 @@ __global__ __launch_bounds__(kTileWaves * 64) void heinsen_scan_tiles(TileParams
     st = seg_apply<SIGNED>(st, seg_combine<SIGNED>(wave_excl, lane_excl));
     lane_emit<SIGNED, LOG_OUT, ITEMS, VECIO>(p.out + row * p.n, start, p.n, st, Av, Mv, sw);
 
-    if (MULTI) {
-        // the last workgroup to finish restores the zeros in the flag region
-        __syncthreads();
-        if (threadIdx.x == 0) {
-            order_release();
-            uint32_t prev = __hip_atomic_fetch_add(&p.counters[1], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            s_last = (prev == p.ntiles - 1u) ? 1u : 0u;
-        }
-        __syncthreads();
-        if (s_last) {
-            for (uint32_t i = threadIdx.x; i < p.nflags; i += NW * 64) p.agg_flag[i] = 0u; // st_flag follows agg_flag
-            if (threadIdx.x == 0) {
-                p.counters[0] = 0u;
-                p.counters[1] = 0u;
-            }
-        }
-    }
 }
 
 // ---- host side -------------------------------------------------------------------------------------------
@@ -460,7 +450,6 @@ hipError_t launch_mode(const ScanCall &c, const BdnPlan &pl, char *flags, char *
     p.tpr = pl.tpr;
     p.gpr = pl.gpr;
     p.ntiles = pl.ntiles;
-    p.nflags = pl.multi ? (uint32_t)(pl.ntiles + pl.rows * pl.gpr) : 0u;
     p.counters = reinterpret_cast<uint32_t *>(flags);
     p.agg_flag = reinterpret_cast<uint32_t *>(flags + pl.off_agg_flag);
     p.st_flag = reinterpret_cast<uint32_t *>(flags + pl.off_st_flag);

@@ -18,7 +18,6 @@
 namespace hs {
 namespace {
 
-constexpr int kGroup = 8; // tiles per group along time
 
 struct BndParams {
     const void *a;
@@ -31,8 +30,7 @@ struct BndParams {
     int ncols;         // B * cols_per_b
     int nchunks;       // ceil(n / (NW*T))
     uint32_t ntiles;   // ncols * nchunks
-    uint32_t nflags;   // number of 32-bit words in the flag region (after the two counters)
-    uint32_t *counters; // [0] ticket, [1] done
+    uint32_t *counters; // [0] ticket
     uint32_t *agg_flag; // [ntiles]
     uint32_t *st_flag;  // [ngroups * ncols]
     float *agg_A;       // [ntiles * CH]
@@ -40,7 +38,21 @@ struct BndParams {
     uint32_t *agg_S;    // bit0: sign of 2^A factor, bit1: sign of 2^M term
     float *st_L;        // [ngroups * ncols * CH] state at the start of a group
     uint32_t *st_S;
+#ifdef HS_TRACE
+    unsigned long long *trace; // [ntiles][8] wall-clock stamps of wave 0 (100 MHz), development only
+#endif
 };
+
+#ifdef HS_TRACE
+#define HS_STAMP(i)                                                              \
+    do {                                                                         \
+        if (threadIdx.x == 0) p.trace[(size_t)tile * 8 + (i)] = wall_clock64(); \
+    } while (0)
+#else
+#define HS_STAMP(i) \
+    do {            \
+    } while (0)
+#endif
 
 template <typename InT, int VEC>
 __device__ __forceinline__ void load_vec(const InT *p, float (&v)[VEC])
@@ -74,13 +86,16 @@ __device__ __forceinline__ void unpack_signs(uint32_t s, Seg &g)
     g.sM = s << 30;
 }
 
-template <bool SIGNED, bool LOG_IN, bool LOG_OUT, typename InT, int VEC, int T, int NW, int MINW = 1>
+// VEC channels per lane, T steps per wave, NW waves per workgroup, G tiles per group along time,
+// MINW waves per SIMD the register allocation must allow, SB: keep the scheduler from hoisting work
+// across time steps (bounds register pressure).
+template <bool SIGNED, bool LOG_IN, bool LOG_OUT, typename InT, int VEC, int T, int NW, int G, int MINW, bool SB>
 __global__ __launch_bounds__(NW * 64, MINW) void heinsen_scan_bnd(BndParams p)
 {
+    constexpr int kGroup = G;
     constexpr int CH = 64 * VEC;
     static_assert(T <= 32, "one sign word per channel");
     __shared__ uint32_t s_tile;
-    __shared__ uint32_t s_last;
     __shared__ float lds_A[NW][CH];
     __shared__ float lds_M[NW][CH];
     __shared__ uint32_t lds_S[NW][CH];
@@ -88,24 +103,44 @@ __global__ __launch_bounds__(NW * 64, MINW) void heinsen_scan_bnd(BndParams p)
     __shared__ uint32_t lds_startS[CH];
 
     const int lane = threadIdx.x & 63;
-    const int w = threadIdx.x >> 6;
+    const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6); // wave-uniform, kept in an SGPR
 
     // Tiles are handed out in start order, so every tile a workgroup may wait for (same column,
     // earlier chunk => smaller ticket) belongs to a workgroup that is already running.
-    if (threadIdx.x == 0) s_tile = atomicAdd(&p.counters[0], 1u);
+    // Whoever draws the last ticket puts the counter back to zero for the next launch.
+    if (threadIdx.x == 0) {
+        const uint32_t tk = atomicAdd(&p.counters[0], 1u);
+        if (tk == p.ntiles - 1u) pub_u(&p.counters[0], 0u);
+        s_tile = tk;
+    }
     __syncthreads();
-    const uint32_t tile = s_tile;
+    const uint32_t tile = __builtin_amdgcn_readfirstlane(s_tile);
+    HS_STAMP(0);
     const int chunk = (int)(tile / (uint32_t)p.ncols);
     const int col = (int)(tile % (uint32_t)p.ncols);
     const int bidx = col / p.cols_per_b;
     const int cg = col % p.cols_per_b;
 
-    const int64_t d0 = (int64_t)cg * CH + (int64_t)lane * VEC;
+    const int loff = lane * VEC;                       // the only per-lane part of every address
+    const int64_t d0 = (int64_t)cg * CH + loff;
     const bool chan_ok = d0 < p.D; // D is a multiple of VEC, so the whole vector is in range
     const int64_t t0 = (int64_t)chunk * (NW * T) + (int64_t)w * T;
-    const int64_t base = ((int64_t)bidx * p.n + t0) * p.D + d0;
-    const InT *ap = reinterpret_cast<const InT *>(p.a) + base;
-    const InT *bp = reinterpret_cast<const InT *>(p.b) + base;
+    const int64_t ubase = ((int64_t)bidx * p.n + t0) * p.D + (int64_t)cg * CH; // wave-uniform
+    const InT *ap = reinterpret_cast<const InT *>(p.a) + ubase;
+    const InT *bp = reinterpret_cast<const InT *>(p.b) + ubase;
+
+    // ---- wave 0 looks at the flags of the records it will need before anything else is in flight: if
+    //      the earlier tiles of the group have already published (the usual case once the kernel is past
+    //      its first round), the records are fetched behind the tile's own loads and cost no latency ----
+    const int g = chunk / kGroup;
+    const int r = chunk % kGroup;
+    const bool more = chunk + 1 < p.nchunks;
+    const bool need_agg = (w == 0) && (lane < r);
+    const bool need_st = (w == 0) && (lane == 63) && (g > 0);
+    uint32_t *const fp = need_agg ? &p.agg_flag[(size_t)(g * kGroup + lane) * p.ncols + col]
+                                  : &p.st_flag[(size_t)g * p.ncols + col];
+    uint32_t early_flag = 1u;
+    if (need_agg || need_st) early_flag = get_u(fp);
 
     // ---- load: the lane's T x VEC inputs -------------------------------------------------------
     float Av[T][VEC], Mv[T][VEC];
@@ -114,15 +149,15 @@ __global__ __launch_bounds__(NW * 64, MINW) void heinsen_scan_bnd(BndParams p)
     if (chan_ok && t0 + T <= p.n) {
 #pragma unroll
         for (int k = 0; k < T; ++k) {
-            load_vec<InT>(ap + (int64_t)k * p.D, Av[k]);
-            load_vec<InT>(bp + (int64_t)k * p.D, Mv[k]);
+            load_vec<InT>(ap + (int64_t)k * p.D + loff, Av[k]);
+            load_vec<InT>(bp + (int64_t)k * p.D + loff, Mv[k]);
         }
     } else {
 #pragma unroll
         for (int k = 0; k < T; ++k) {
             if (chan_ok && t0 + k < p.n) {
-                load_vec<InT>(ap + (int64_t)k * p.D, Av[k]);
-                load_vec<InT>(bp + (int64_t)k * p.D, Mv[k]);
+                load_vec<InT>(ap + (int64_t)k * p.D + loff, Av[k]);
+                load_vec<InT>(bp + (int64_t)k * p.D + loff, Mv[k]);
             } else {
 #pragma unroll
                 for (int v = 0; v < VEC; ++v) {
@@ -131,6 +166,36 @@ __global__ __launch_bounds__(NW * 64, MINW) void heinsen_scan_bnd(BndParams p)
                 }
             }
         }
+    }
+
+    float fA[kGroup > 1 ? kGroup - 1 : 1][VEC], fM[kGroup > 1 ? kGroup - 1 : 1][VEC], gL[VEC];
+    uint32_t fS[kGroup > 1 ? kGroup - 1 : 1][VEC], gS[VEC];
+    bool have_records = false;
+    auto fetch_records = [&]() {
+        if (g > 0) {
+            const size_t si = ((size_t)g * p.ncols + col) * CH + (size_t)lane * VEC;
+#pragma unroll
+            for (int v = 0; v < VEC; ++v) {
+                gL[v] = get_f(&p.st_L[si + v]);
+                gS[v] = SIGNED ? get_u(&p.st_S[si + v]) : 0u;
+            }
+        }
+#pragma unroll
+        for (int j = 0; j < kGroup - 1; ++j) {
+            if (j < r) {
+                const size_t ti = ((size_t)(g * kGroup + j) * p.ncols + col) * CH + (size_t)lane * VEC;
+#pragma unroll
+                for (int v = 0; v < VEC; ++v) {
+                    fA[j][v] = get_f(&p.agg_A[ti + v]);
+                    fM[j][v] = get_f(&p.agg_M[ti + v]);
+                    fS[j][v] = SIGNED ? get_u(&p.agg_S[ti + v]) : 0u;
+                }
+            }
+        }
+    };
+    if (w == 0) {
+        have_records = __builtin_amdgcn_ballot_w64(early_flag == 0u) == 0ull;
+        if (have_records) fetch_records(); // issued after the flags were seen set: a real dependency
     }
 
     // ---- encode + serial scan in each lane; Av/Mv become the per-element records (see stash) --------
@@ -156,8 +221,10 @@ __global__ __launch_bounds__(NW * 64, MINW) void heinsen_scan_bnd(BndParams p)
             }
             stash<SIGNED, LOG_OUT>(run[v], k, Av[k][v], Mv[k][v], sw[v]);
         }
+        if (SB) __builtin_amdgcn_sched_barrier(0);
     }
 
+    HS_STAMP(1);
     // ---- chain the waves of the workgroup through LDS ------------------------------------------
 #pragma unroll
     for (int v = 0; v < VEC; ++v) {
@@ -193,9 +260,7 @@ __global__ __launch_bounds__(NW * 64, MINW) void heinsen_scan_bnd(BndParams p)
 
     // ---- wave 0: publish the tile summary, obtain the state at the start of the tile -------------
     if (w == 0) {
-        const int g = chunk / kGroup;
-        const int r = chunk % kGroup;
-        const bool more = chunk + 1 < p.nchunks;
+        HS_STAMP(2);
         const size_t my = (size_t)tile * CH + (size_t)lane * VEC;
         if (more && r < kGroup - 1) {
 #pragma unroll
@@ -205,23 +270,24 @@ __global__ __launch_bounds__(NW * 64, MINW) void heinsen_scan_bnd(BndParams p)
                 if (SIGNED) pub_u(&p.agg_S[my + v], pack_signs(pre[v]));
             }
             order_release();
-            if (lane == 0) __hip_atomic_store(&p.agg_flag[tile], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            // A flag holds the number of tiles that will still read the record; each reader takes one
+            // off after its read, so the flag is back at zero when the kernel ends.
+            const int last_in_group = min(g * kGroup + kGroup - 1, p.nchunks - 1);
+            if (lane == 0) pub_u(&p.agg_flag[tile], (uint32_t)(last_in_group - chunk));
         }
 
-        // wait for the r earlier tiles of the group (lanes 0..r-1) and for the group's start state
-        // (lane 63), all polls in flight together
-        {
-            const bool need_agg = lane < r;
-            const bool need_st = (lane == 63) && (g > 0);
-            const uint32_t *fp = need_agg ? &p.agg_flag[(size_t)(g * kGroup + lane) * p.ncols + col]
-                                          : &p.st_flag[(size_t)g * p.ncols + col];
+        HS_STAMP(3);
+        if (!have_records) {
+            // wait for the r earlier tiles of the group (lanes 0..r-1) and for the group's start state
+            // (lane 63), all polls in flight together
             if (need_agg || need_st) {
-                while (__hip_atomic_load(fp, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == 0u)
-                    __builtin_amdgcn_s_sleep(2);
+                while (get_u(fp) == 0u) __builtin_amdgcn_s_sleep(2);
             }
             order_acquire();
+            fetch_records();
         }
 
+        HS_STAMP(4);
         State st[VEC];
         if (g == 0) {
 #pragma unroll
@@ -231,41 +297,24 @@ __global__ __launch_bounds__(NW * 64, MINW) void heinsen_scan_bnd(BndParams p)
                 encode<SIGNED, LOG_IN>(x0v, st[v].lx, st[v].s);
             }
         } else {
-            const size_t si = ((size_t)g * p.ncols + col) * CH + (size_t)lane * VEC;
 #pragma unroll
             for (int v = 0; v < VEC; ++v) {
-                st[v].lx = get_f(&p.st_L[si + v]);
-                st[v].s = SIGNED ? get_u(&p.st_S[si + v]) : 0u;
+                st[v].lx = gL[v];
+                st[v].s = gS[v];
             }
         }
-        if (r > 0) {
-            // all payload loads first (independent), then the fold in tile order
-            float fA[kGroup - 1][VEC], fM[kGroup - 1][VEC];
-            uint32_t fS[kGroup - 1][VEC];
+        // fold the earlier tiles of the group in tile order
 #pragma unroll
-            for (int j = 0; j < kGroup - 1; ++j) {
-                if (j < r) {
-                    const size_t ti = ((size_t)(g * kGroup + j) * p.ncols + col) * CH + (size_t)lane * VEC;
+        for (int j = 0; j < kGroup - 1; ++j) {
+            if (j < r) {
 #pragma unroll
-                    for (int v = 0; v < VEC; ++v) {
-                        fA[j][v] = get_f(&p.agg_A[ti + v]);
-                        fM[j][v] = get_f(&p.agg_M[ti + v]);
-                        fS[j][v] = SIGNED ? get_u(&p.agg_S[ti + v]) : 0u;
-                    }
-                }
-            }
-#pragma unroll
-            for (int j = 0; j < kGroup - 1; ++j) {
-                if (j < r) {
-#pragma unroll
-                    for (int v = 0; v < VEC; ++v) {
-                        Seg h;
-                        h.A = fA[j][v];
-                        h.M = fM[j][v];
-                        h.sA = h.sM = 0u;
-                        if (SIGNED) unpack_signs(fS[j][v], h);
-                        st[v] = seg_apply<SIGNED>(st[v], h);
-                    }
+                for (int v = 0; v < VEC; ++v) {
+                    Seg h;
+                    h.A = fA[j][v];
+                    h.M = fM[j][v];
+                    h.sA = h.sM = 0u;
+                    if (SIGNED) unpack_signs(fS[j][v], h);
+                    st[v] = seg_apply<SIGNED>(st[v], h);
                 }
             }
         }
@@ -274,6 +323,7 @@ __global__ __launch_bounds__(NW * 64, MINW) void heinsen_scan_bnd(BndParams p)
             lds_startL[lane * VEC + v] = st[v].lx;
             lds_startS[lane * VEC + v] = st[v].s;
         }
+        HS_STAMP(5);
         // last tile of a group: the state after this tile starts the next group
         if (more && r == kGroup - 1) {
             const size_t si = ((size_t)(g + 1) * p.ncols + col) * CH + (size_t)lane * VEC;
@@ -284,13 +334,13 @@ __global__ __launch_bounds__(NW * 64, MINW) void heinsen_scan_bnd(BndParams p)
                 if (SIGNED) pub_u(&p.st_S[si + v], nx.s);
             }
             order_release();
-            if (lane == 0)
-                __hip_atomic_store(&p.st_flag[(size_t)(g + 1) * p.ncols + col], 1u, __ATOMIC_RELAXED,
-                                   __HIP_MEMORY_SCOPE_AGENT);
+            const int next_group_tiles = min(kGroup, p.nchunks - (g + 1) * kGroup);
+            if (lane == 0) pub_u(&p.st_flag[(size_t)(g + 1) * p.ncols + col], (uint32_t)next_group_tiles);
         }
     }
     __syncthreads();
 
+    HS_STAMP(6);
     // ---- state at the start of this wave's steps, then every element -----------------------------
     State st[VEC];
 #pragma unroll
@@ -299,7 +349,7 @@ __global__ __launch_bounds__(NW * 64, MINW) void heinsen_scan_bnd(BndParams p)
         st[v].s = lds_startS[lane * VEC + v];
         if (w > 0) st[v] = seg_apply<SIGNED>(st[v], pre[v]);
     }
-    float *op = p.out + base;
+    float *op = p.out + ubase;
     const bool full = chan_ok && t0 + T <= p.n;
     uint32_t swx[VEC];
 #pragma unroll
@@ -309,62 +359,79 @@ __global__ __launch_bounds__(NW * 64, MINW) void heinsen_scan_bnd(BndParams p)
         float o[VEC];
 #pragma unroll
         for (int v = 0; v < VEC; ++v) o[v] = emit<SIGNED, LOG_OUT>(st[v], Av[k][v], Mv[k][v], swx[v], k);
-        if (full || (chan_ok && t0 + k < p.n)) store_vec(op + (int64_t)k * p.D, o);
+        if (full || (chan_ok && t0 + k < p.n)) store_vec(op + (int64_t)k * p.D + loff, o);
+        if (SB) __builtin_amdgcn_sched_barrier(0);
     }
 
-    // ---- the last workgroup to finish restores the zeros in the flag region ------------------------
-    __syncthreads(); // wave 0's polls are over before this workgroup reports completion
-    if (threadIdx.x == 0) {
-        order_release();
-        uint32_t prev = __hip_atomic_fetch_add(&p.counters[1], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        s_last = (prev == p.ntiles - 1u) ? 1u : 0u;
-    }
-    __syncthreads();
-    if (s_last) {
-        for (uint32_t i = threadIdx.x; i < p.nflags; i += NW * 64) p.agg_flag[i] = 0u; // agg_flag and st_flag are contiguous
-        if (threadIdx.x == 0) {
-            p.counters[0] = 0u;
-            p.counters[1] = 0u;
-        }
-    }
+    HS_STAMP(7);
+    // Take this tile off the reader counts of the records it used (nothing waits for these).
+    if (need_agg || need_st) (void)__hip_atomic_fetch_sub(fp, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
 // ---- host side ------------------------------------------------------------------------------------
 
+#ifdef HS_TRACE
+unsigned long long *g_trace = nullptr;
+#endif
+
 struct BndPlan {
-    int vec, T, NW, CH, variant;
+    int vec, T, NW, G, CH, variant;
     int cols_per_b, ncols, nchunks, ngroups;
     uint32_t ntiles;
     size_t off_agg_flag, off_st_flag, flag_bytes;                      // inside the flag buffer
     size_t off_agg_A, off_agg_M, off_agg_S, off_st_L, off_st_S, data_bytes; // inside the data buffer
 };
 
+#ifdef HS_TUNING
+// tuning variants (signed float32 only, development builds): ID, VEC, T, NW, G, MINW, SB
+#define HS_VARIANTS(X) \
+    X(1, 2, 16, 8, 8, 2, false) X(2, 2, 16, 8, 4, 2, false) X(3, 1, 16, 16, 2, 8, true) X(4, 1, 16, 16, 8, 8, true) \
+    X(5, 1, 32, 16, 4, 4, true) X(6, 1, 32, 8, 4, 4, true) X(7, 1, 32, 8, 2, 4, true) X(8, 1, 32, 8, 8, 4, true) \
+    X(9, 1, 16, 16, 4, 8, false) X(10, 1, 24, 8, 4, 6, true) X(11, 1, 24, 16, 4, 6, true) X(12, 1, 8, 16, 4, 8, true) \
+    X(13, 1, 32, 8, 4, 5, true) X(14, 1, 16, 16, 4, 8, true) X(15, 1, 16, 8, 4, 8, true) X(16, 1, 20, 16, 4, 6, true)
+constexpr int kVariants[][4] = {{0, 0, 0, 0},
+#define X(ID, V, T_, NW_, G_, MW, SB_) {V, T_, NW_, G_},
+                                HS_VARIANTS(X)
+#undef X
+};
+constexpr int kNumVariants = sizeof(kVariants) / sizeof(kVariants[0]);
+#endif
+
 BndPlan make_plan(const ScanCall &c)
 {
     BndPlan pl;
     const size_t in_sz = c.bf16 ? 2 : 4;
     auto aligned = [](const void *ptr, size_t a) { return (reinterpret_cast<uintptr_t>(ptr) % a) == 0; };
+    // float32: one channel per lane, 16 steps per wave, 16 waves (tile = 64 channels x 256 steps, 62
+    // VGPRs, two workgroups per CU) measured best on MI355X; bf16 takes two channels per lane so that a
+    // wave still reads 256 contiguous bytes per step.
     pl.vec = 1;
-    if (c.D % 2 == 0 && aligned(c.a, 2 * in_sz) && aligned(c.b, 2 * in_sz) && aligned(c.out, 8)) pl.vec = 2;
     pl.T = 16;
-    pl.NW = 8;
+    pl.NW = 16;
+    pl.G = 4;
+    if (c.bf16 && c.D % 2 == 0 && aligned(c.a, 2 * in_sz) && aligned(c.b, 2 * in_sz) && aligned(c.out, 8)) {
+        pl.vec = 2;
+        pl.NW = 8;
+    }
     pl.variant = 0;
+#ifdef HS_TUNING
     if (const char *ev = getenv("HEINSEN_BND_VARIANT")) {
         pl.variant = atoi(ev);
-        static const int tab[][3] = {{0, 0, 0}, {2, 16, 8}, {2, 16, 4}, {2, 8, 8}, {4, 8, 8}, {4, 8, 4}, {1, 32, 4}, {2, 32, 4}, {1, 16, 8}, {4, 4, 16}, {2, 8, 16}};
-        if (pl.variant >= 1 && pl.variant <= 10 && c.is_signed && !c.bf16 && c.D % 4 == 0) {
-            pl.vec = tab[pl.variant][0];
-            pl.T = tab[pl.variant][1];
-            pl.NW = tab[pl.variant][2];
+        if (pl.variant >= 1 && pl.variant < kNumVariants && c.is_signed && !c.bf16 && c.D % 4 == 0) {
+            pl.vec = kVariants[pl.variant][0];
+            pl.T = kVariants[pl.variant][1];
+            pl.NW = kVariants[pl.variant][2];
+            pl.G = kVariants[pl.variant][3];
         } else {
             pl.variant = 0;
         }
     }
+#endif
     pl.CH = 64 * pl.vec;
     pl.cols_per_b = (int)ceil_div(c.D, pl.CH);
     pl.ncols = (int)(c.B * pl.cols_per_b);
     pl.nchunks = (int)ceil_div(c.n, (int64_t)pl.NW * pl.T);
-    pl.ngroups = (int)ceil_div(pl.nchunks, kGroup);
+    pl.ngroups = (int)ceil_div(pl.nchunks, pl.G);
     pl.ntiles = (uint32_t)pl.ncols * (uint32_t)pl.nchunks;
     size_t off = 64; // counters
     pl.off_agg_flag = off;
@@ -399,7 +466,6 @@ hipError_t launch_mode(const ScanCall &c, const BndPlan &pl, char *flags, char *
     p.ncols = pl.ncols;
     p.nchunks = pl.nchunks;
     p.ntiles = pl.ntiles;
-    p.nflags = (uint32_t)((pl.off_st_flag - pl.off_agg_flag) / 4 + (size_t)pl.ngroups * pl.ncols);
     p.counters = reinterpret_cast<uint32_t *>(flags);
     p.agg_flag = reinterpret_cast<uint32_t *>(flags + pl.off_agg_flag);
     p.st_flag = reinterpret_cast<uint32_t *>(flags + pl.off_st_flag);
@@ -408,29 +474,27 @@ hipError_t launch_mode(const ScanCall &c, const BndPlan &pl, char *flags, char *
     p.agg_S = reinterpret_cast<uint32_t *>(data + pl.off_agg_S);
     p.st_L = reinterpret_cast<float *>(data + pl.off_st_L);
     p.st_S = reinterpret_cast<uint32_t *>(data + pl.off_st_S);
+#ifdef HS_TRACE
+    if (!g_trace) (void)hipMalloc(&g_trace, (size_t)(1u << 20) * 8 * sizeof(unsigned long long));
+    p.trace = g_trace;
+#endif
     dim3 grid(pl.ntiles), block(pl.NW * 64);
+#ifdef HS_TUNING
     if constexpr (SIGNED && sizeof(InT) == 4) {
-#define HS_VAR(ID, V, T_, NW_, MW)                                                                                 \
-    if (pl.variant == ID) {                                                                                        \
-        hipLaunchKernelGGL((heinsen_scan_bnd<SIGNED, LOG_IN, LOG_OUT, InT, V, T_, NW_, MW>), grid, block, 0, c.stream, p); \
-        return hipGetLastError();                                                                                  \
+#define X(ID, V, T_, NW_, G_, MW, SB_)                                                                                 \
+    if (pl.variant == ID) {                                                                                            \
+        hipLaunchKernelGGL((heinsen_scan_bnd<SIGNED, LOG_IN, LOG_OUT, InT, V, T_, NW_, G_, MW, SB_>), grid, block, 0,  \
+                           c.stream, p);                                                                               \
+        return hipGetLastError();                                                                                      \
     }
-        HS_VAR(1, 2, 16, 8, 2)
-        HS_VAR(2, 2, 16, 4, 2)
-        HS_VAR(3, 2, 8, 8, 2)
-        HS_VAR(4, 4, 8, 8, 2)
-        HS_VAR(5, 4, 8, 4, 2)
-        HS_VAR(6, 1, 32, 4, 2)
-        HS_VAR(7, 2, 32, 4, 1)
-        HS_VAR(8, 1, 16, 8, 2)
-        HS_VAR(9, 4, 4, 16, 4)
-        HS_VAR(10, 2, 8, 16, 4)
-#undef HS_VAR
+        HS_VARIANTS(X)
+#undef X
     }
+#endif
     if (pl.vec == 2)
-        hipLaunchKernelGGL((heinsen_scan_bnd<SIGNED, LOG_IN, LOG_OUT, InT, 2, 16, 8>), grid, block, 0, c.stream, p);
+        hipLaunchKernelGGL((heinsen_scan_bnd<SIGNED, LOG_IN, LOG_OUT, InT, 2, 16, 8, 4, 4, true>), grid, block, 0, c.stream, p);
     else
-        hipLaunchKernelGGL((heinsen_scan_bnd<SIGNED, LOG_IN, LOG_OUT, InT, 1, 16, 8>), grid, block, 0, c.stream, p);
+        hipLaunchKernelGGL((heinsen_scan_bnd<SIGNED, LOG_IN, LOG_OUT, InT, 1, 16, 16, 4, 8, true>), grid, block, 0, c.stream, p);
     return hipGetLastError();
 }
 
@@ -454,5 +518,12 @@ hipError_t bnd_launch(const ScanCall &c, void *flags, void *data)
 }
 
 const char *bnd_kernel_name(const ScanCall &) { return "heinsen_scan_bnd"; }
+
+#ifdef HS_TRACE
+extern "C" int heinsen_debug_trace(unsigned long long *host, size_t ntiles)
+{
+    return (int)hipMemcpy(host, g_trace, ntiles * 8 * sizeof(unsigned long long), hipMemcpyDeviceToHost);
+}
+#endif
 
 } // namespace hs
