@@ -131,26 +131,134 @@ struct RowsParams {
     int x0_stride;
 };
 
-template <bool SIGNED, bool LOG_IN, bool LOG_OUT, typename InT, int ITEMS, bool VECIO>
-__global__ __launch_bounds__(256) void heinsen_scan_rows_wave(RowsParams p)
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
+// A wave moves a row between global memory and its lanes through a private LDS region so that global
+// accesses are coalesced (consecutive lanes touch consecutive 16-byte vectors) while each lane ends up
+// with NV consecutive vectors of the row ("blocked").  Vector c of the row lives at slot c + c/NV: one
+// empty slot after every lane's NV slots keeps both access patterns free of bank conflicts.  LDS
+// operations of one wave execute in order, so only the compiler has to be kept from reordering them.
+__device__ __forceinline__ void wave_lds_order() { asm volatile("" ::: "memory"); __builtin_amdgcn_wave_barrier(); }
+
+// Global (striped, coalesced) -> lanes (blocked).  Vectors at or beyond n_vec are replaced by `fill`.
+template <int NV>
+__device__ __forceinline__ void wave_load_blocked(const u32x4 *row, int64_t n_vec, u32x4 fill, u32x4 *lds, int lane,
+                                                  u32x4 (&v)[NV])
 {
+    if (NV == 1) {
+        v[0] = (lane < n_vec) ? row[lane] : fill;
+        return;
+    }
+    u32x4 t[NV];
+#pragma unroll
+    for (int j = 0; j < NV; ++j) {
+        const int c = j * 64 + lane;
+        t[j] = (c < n_vec) ? row[c] : fill;
+    }
+#pragma unroll
+    for (int j = 0; j < NV; ++j) {
+        const int c = j * 64 + lane;
+        lds[c + c / NV] = t[j];
+    }
+    wave_lds_order();
+#pragma unroll
+    for (int q = 0; q < NV; ++q) v[q] = lds[lane * (NV + 1) + q];
+    wave_lds_order();
+}
+
+// Lanes (blocked) -> global (striped, coalesced).
+template <int NV>
+__device__ __forceinline__ void wave_store_blocked(u32x4 *row, int64_t n_vec, u32x4 *lds, int lane, const u32x4 (&v)[NV])
+{
+#pragma unroll
+    for (int q = 0; q < NV; ++q) lds[lane * (NV + 1) + q] = v[q];
+    wave_lds_order();
+    u32x4 t[NV];
+#pragma unroll
+    for (int j = 0; j < NV; ++j) {
+        const int c = j * 64 + lane;
+        t[j] = lds[c + c / NV];
+    }
+#pragma unroll
+    for (int j = 0; j < NV; ++j) {
+        const int c = j * 64 + lane;
+        if (c < n_vec) row[c] = t[j];
+    }
+    wave_lds_order();
+}
+
+template <typename InT, int NVI, int ITEMS>
+__device__ __forceinline__ void unpack_inputs(const u32x4 (&v)[NVI], float (&x)[ITEMS])
+{
+    if (sizeof(InT) == 4) {
+#pragma unroll
+        for (int q = 0; q < NVI; ++q)
+#pragma unroll
+            for (int i = 0; i < 4; ++i) x[q * 4 + i] = u2f(v[q][i]);
+    } else {
+#pragma unroll
+        for (int q = 0; q < NVI; ++q)
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                x[q * 8 + 2 * i] = u2f(v[q][i] << 16);
+                x[q * 8 + 2 * i + 1] = u2f(v[q][i] & 0xffff0000u);
+            }
+    }
+}
+
+
+template <bool SIGNED, bool LOG_IN, bool LOG_OUT, typename InT, int ITEMS, bool VECIO>
+__global__ __launch_bounds__(256, VECIO ? 4 : 1) void heinsen_scan_rows_wave(RowsParams p)
+{
+    // 16-byte slots per wave: the output row (ITEMS/4 vectors per lane, the larger of the two) plus padding
+    __shared__ u32x4 stage[VECIO ? 4 : 1][VECIO ? 64 * (ITEMS / 4 + 1) : 1];
     const int lane = threadIdx.x & 63;
-    const int64_t row = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+    const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int64_t row = (int64_t)blockIdx.x * 4 + w;
     if (row >= p.rows) return; // whole wave leaves together
     const InT *arow = reinterpret_cast<const InT *>(p.a) + row * p.n;
     const InT *brow = reinterpret_cast<const InT *>(p.b) + row * p.n;
+    float *orow = p.out + row * p.n;
     const int64_t start = (int64_t)lane * ITEMS;
 
     float Av[ITEMS], Mv[ITEMS];
     uint32_t sw;
-    lane_load<LOG_IN, InT, ITEMS, VECIO>(arow, brow, start, p.n, Av, Mv);
+    if (VECIO) {
+        constexpr int VL = 16 / (int)sizeof(InT);
+        constexpr int NVI = ITEMS / VL;
+        static_assert(ITEMS % VL == 0 && NVI >= 1 && NVI <= 8, "lane chunk must be 1..8 vectors");
+        // a = 1, b = 0 (log domain: 0, -inf) for the steps past the end of the row
+        const uint32_t one = sizeof(InT) == 4 ? 0x3f800000u : 0x3f803f80u;
+        const uint32_t ninf = sizeof(InT) == 4 ? 0xff800000u : 0xff80ff80u;
+        const uint32_t fa = LOG_IN ? 0u : one, fb = LOG_IN ? ninf : 0u;
+        const int64_t n_vec = p.n / VL;
+        u32x4 va[NVI], vb[NVI];
+        wave_load_blocked<NVI>(reinterpret_cast<const u32x4 *>(arow), n_vec, u32x4{fa, fa, fa, fa}, stage[w], lane, va);
+        wave_load_blocked<NVI>(reinterpret_cast<const u32x4 *>(brow), n_vec, u32x4{fb, fb, fb, fb}, stage[w], lane, vb);
+        unpack_inputs<InT, NVI, ITEMS>(va, Av);
+        unpack_inputs<InT, NVI, ITEMS>(vb, Mv);
+    } else {
+        lane_load<LOG_IN, InT, ITEMS, false>(arow, brow, start, p.n, Av, Mv);
+    }
     Seg mine = lane_scan<SIGNED, LOG_IN, LOG_OUT, ITEMS>(Av, Mv, sw);
     Seg excl = wave_shift_up<SIGNED>(wave_inclusive_scan<SIGNED>(mine));
 
     State st;
     encode<SIGNED, LOG_IN>(p.x0[p.x0_stride ? row : 0], st.lx, st.s);
     st = seg_apply<SIGNED>(st, excl);
-    lane_emit<SIGNED, LOG_OUT, ITEMS, VECIO>(p.out + row * p.n, start, p.n, st, Av, Mv, sw);
+    if (VECIO) {
+        constexpr int NVO = ITEMS / 4;
+        const uint32_t swx = fold_state_sign<SIGNED>(sw, st);
+        u32x4 vo[NVO];
+#pragma unroll
+        for (int q = 0; q < NVO; ++q)
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+                vo[q][i] = f2u(emit<SIGNED, LOG_OUT>(st, Av[q * 4 + i], Mv[q * 4 + i], swx, q * 4 + i));
+        wave_store_blocked<NVO>(reinterpret_cast<u32x4 *>(orow), p.n / 4, stage[w], lane, vo);
+    } else {
+        lane_emit<SIGNED, LOG_OUT, ITEMS, false>(orow, start, p.n, st, Av, Mv, sw);
+    }
 }
 
 // ---- tiles with a chained carry ------------------------------------------------------------------------
