@@ -127,6 +127,8 @@ def main() -> int:
     ap.add_argument("--workload", type=int, default=2, help="benchmark configuration 1..5 (default 2)")
     ap.add_argument("--no-others", action="store_true", help="time only the headline workload")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="also run plain device copies of a known size (reference for rocprofv3 FETCH_SIZE/WRITE_SIZE)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU (no sharding, no collectives); use --gpus 1", file=sys.stderr)
@@ -142,6 +144,16 @@ def main() -> int:
         return 3
     hb.load()  # no fallback: raises if the HIP library is missing
     torch.cuda.set_device(0)
+
+    if args.copy_calibration:
+        # 5 plain copies of 2^25 float32 (128 MiB read + 128 MiB written each): the HBM byte counters of
+        # this kernel, divided by its known size, give the scale factor for the scan kernel's counters
+        src = torch.ones(1 << 25, dtype=torch.float32, device="cuda")
+        dst = torch.empty_like(src)
+        for _ in range(5):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
 
     cfg = workloads.CONFIGS[args.workload]
     wall_ms, kern_ms, kern_med, kern_min = time_workload(cfg, torch, hb, args.steps, args.warmup)

@@ -15,11 +15,12 @@ constexpr uint32_t kAllFlags =
 
 thread_local int t_last_hip_error = 0;
 
+// One buffer of tagged 64-bit records per (device, stream); see heinsen_internal.hpp.
 struct Scratch {
-    void *flags = nullptr;
-    size_t flag_cap = 0;
-    void *data = nullptr;
-    size_t data_cap = 0;
+    unsigned long long *records = nullptr;
+    size_t capacity = 0;      // in records, including the header
+    uint32_t epoch = 0;       // epoch of the last launch (0: none yet)
+    uint32_t ticket_base = 0; // value of the ticket counter when the next launch starts
 };
 
 std::mutex g_mutex;
@@ -55,52 +56,43 @@ int describe(int64_t B, int64_t D, int64_t n, int layout, uint32_t flags, hs::Sc
     c.log_out = flags & HEINSEN_LOG_OUTPUT;
     c.bf16 = flags & HEINSEN_IN_BF16;
     c.x0_scalar = flags & HEINSEN_X0_SCALAR;
-    c.vec_ok = false;
     // [B, n, 1] is the same memory as [B, 1, n]: a single channel per batch item is a plain row
     bnd = (layout == HEINSEN_LAYOUT_BND) && D > 1;
     return HEINSEN_OK;
 }
 
-int get_scratch(hipStream_t stream, const hs::ScratchNeed &need, Scratch &out)
+// Makes sure the stream's record buffer can hold `need`, and hands out the tag of the next launch.
+// Called with g_mutex held; the caller keeps it until the kernel is enqueued so that launches enter
+// the stream in epoch order.
+int prepare_launch(hipStream_t stream, const hs::ScratchNeed &need, Scratch *&out, hs::LaunchTag &tag)
 {
-    out = Scratch();
-    if (need.flag_bytes == 0 && need.data_bytes == 0) return HEINSEN_OK;
     int dev = 0;
     if (!hip_ok(hipGetDevice(&dev))) return HEINSEN_ERR_HIP;
-    std::lock_guard<std::mutex> lock(g_mutex);
     Scratch &s = g_scratch[std::make_pair(dev, stream)];
-    if (s.flag_cap < need.flag_bytes) {
-        // work queued on the old buffer must drain before it is replaced
-        if (s.flags) {
-            if (!hip_ok(hipStreamSynchronize(stream))) return HEINSEN_ERR_HIP;
-            (void)hipFree(s.flags);
-            s.flags = nullptr;
-            s.flag_cap = 0;
+    const size_t want = hs::kRecordBase + need.records;
+    const bool wrap = s.epoch >= 0x3ffffffeu; // 30-bit epochs: start over on a cleared buffer
+    if (s.capacity < want || wrap) {
+        // work queued on the old buffer must drain before it is replaced or cleared
+        if (s.records && !hip_ok(hipStreamSynchronize(stream))) return HEINSEN_ERR_HIP;
+        if (s.capacity < want) {
+            if (s.records) (void)hipFree(s.records);
+            s.records = nullptr;
+            s.capacity = 0;
+            const size_t cap = hs::align_up(want + want / 2, 512);
+            void *ptr = nullptr;
+            if (!hip_ok(hipMalloc(&ptr, cap * sizeof(unsigned long long)))) return HEINSEN_ERR_ALLOC;
+            s.records = static_cast<unsigned long long *>(ptr);
+            s.capacity = cap;
         }
-        size_t cap = hs::align_up(need.flag_bytes + need.flag_bytes / 2, 4096);
-        void *ptr = nullptr;
-        if (!hip_ok(hipMalloc(&ptr, cap))) return HEINSEN_ERR_ALLOC;
-        if (!hip_ok(hipMemset(ptr, 0, cap))) {
-            (void)hipFree(ptr);
-            return HEINSEN_ERR_HIP;
-        }
-        s.flags = ptr;
-        s.flag_cap = cap;
+        if (!hip_ok(hipMemset(s.records, 0, s.capacity * sizeof(unsigned long long)))) return HEINSEN_ERR_HIP;
+        s.epoch = 0;
+        s.ticket_base = 0;
     }
-    if (s.data_cap < need.data_bytes) {
-        if (s.data) {
-            if (!hip_ok(hipStreamSynchronize(stream))) return HEINSEN_ERR_HIP;
-            (void)hipFree(s.data);
-            s.data = nullptr;
-            s.data_cap = 0;
-        }
-        size_t cap = hs::align_up(need.data_bytes + need.data_bytes / 2, 4096);
-        void *ptr = nullptr;
-        if (!hip_ok(hipMalloc(&ptr, cap))) return HEINSEN_ERR_ALLOC;
-        s.data = ptr;
-        s.data_cap = cap;
-    }
-    out = s;
+    s.epoch += 1;
+    tag.epoch = s.epoch;
+    tag.ticket_base = s.ticket_base;
+    s.ticket_base += need.tickets; // wraps modulo 2^32 together with the device counter
+    out = &s;
     return HEINSEN_OK;
 }
 
@@ -127,10 +119,21 @@ int heinsen_scan(const void *a, const void *b, const void *x0, void *out, int64_
     c.stream = static_cast<hipStream_t>(stream);
 
     const hs::ScratchNeed need = bnd ? hs::bnd_scratch(c) : hs::bdn_scratch(c);
-    Scratch s;
-    st = get_scratch(c.stream, need, s);
+    if (need.records == 0 && need.tickets == 0) {
+        hipError_t e = bnd ? hs::bnd_launch(c, nullptr, hs::LaunchTag{0, 0}) : hs::bdn_launch(c, nullptr, hs::LaunchTag{0, 0});
+        return hip_ok(e) ? HEINSEN_OK : HEINSEN_ERR_HIP;
+    }
+    // The carry records are told apart by a per-launch epoch that the host hands out, so a launch that
+    // is recorded once and replayed many times (HIP graph capture) would see its own stale records.
+    hipStreamCaptureStatus cap = hipStreamCaptureStatusNone;
+    if (c.stream != nullptr && hipStreamIsCapturing(c.stream, &cap) == hipSuccess && cap != hipStreamCaptureStatusNone)
+        return HEINSEN_ERR_UNSUPPORTED;
+    std::lock_guard<std::mutex> lock(g_mutex);
+    Scratch *s = nullptr;
+    hs::LaunchTag tag{0, 0};
+    st = prepare_launch(c.stream, need, s, tag);
     if (st != HEINSEN_OK) return st;
-    hipError_t e = bnd ? hs::bnd_launch(c, s.flags, s.data) : hs::bdn_launch(c, s.flags, s.data);
+    hipError_t e = bnd ? hs::bnd_launch(c, s->records, tag) : hs::bdn_launch(c, s->records, tag);
     if (!hip_ok(e)) return HEINSEN_ERR_HIP;
     return HEINSEN_OK;
 }
@@ -163,8 +166,7 @@ int heinsen_release_scratch(void)
             continue;
         }
         (void)hipDeviceSynchronize();
-        if (kv.second.flags) (void)hipFree(kv.second.flags);
-        if (kv.second.data) (void)hipFree(kv.second.data);
+        if (kv.second.records) (void)hipFree(kv.second.records);
     }
     g_scratch.clear();
     if (have_prev) (void)hipSetDevice(prev);

@@ -17,26 +17,32 @@ struct ScanCall {
     bool log_in, log_out; // natural-log inputs / output
     bool bf16;            // a, b stored as bfloat16
     bool x0_scalar;       // one x0 for all sequences
-    bool vec_ok;          // pointers and row pitch allow 16-byte vector access
     hipStream_t stream;
 };
 
-// Scratch comes in two buffers per (device, stream): `flags` holds counters and ready-flags and is
-// all-zero whenever no kernel is running (allocated zeroed; every kernel restores the zeros it
-// disturbed before it finishes), `data` holds the published summaries and may contain anything.
-struct ScratchNeed {
-    size_t flag_bytes;
-    size_t data_bytes;
+// Scratch is one buffer of 64-bit tagged records per (device, stream) (see heinsen_math.hpp): word 0
+// is the ticket counter, carry records start at kRecordBase.  Every launch gets a fresh epoch, so the
+// buffer never needs clearing; `ticket_base` is the value the ticket counter has when the launch
+// starts (the host adds the number of tiles after every launch).
+constexpr size_t kRecordBase = 8;
+
+struct LaunchTag {
+    uint32_t epoch;       // 1 .. 2^30 - 1
+    uint32_t ticket_base; // ticket counter value at launch
 };
 
-// Each path reports how much scratch it needs (either may be 0), launches on call.stream, and names
-// the kernel it would launch.  The layouts inside the two buffers are private to each path.
+// Each path reports how many records it needs beyond kRecordBase (may be 0) and how many tickets a
+// launch draws, launches on call.stream, and names the kernel it would launch.
+struct ScratchNeed {
+    size_t records;
+    uint32_t tickets;
+};
 ScratchNeed bnd_scratch(const ScanCall &c);
-hipError_t bnd_launch(const ScanCall &c, void *flags, void *data);
+hipError_t bnd_launch(const ScanCall &c, unsigned long long *records, LaunchTag tag);
 const char *bnd_kernel_name(const ScanCall &c);
 
 ScratchNeed bdn_scratch(const ScanCall &c);
-hipError_t bdn_launch(const ScanCall &c, void *flags, void *data);
+hipError_t bdn_launch(const ScanCall &c, unsigned long long *records, LaunchTag tag);
 const char *bdn_kernel_name(const ScanCall &c);
 
 static inline int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }

@@ -191,6 +191,29 @@ __device__ __forceinline__ Seg wave_inclusive_scan(Seg g)
     return g;
 }
 
+// Inclusive scan inside each row of 16 lanes (4 steps): lanes 15, 31, 47, 63 end up with the fold of
+// their row, in lane order.
+template <bool SIGNED>
+__device__ __forceinline__ Seg row16_inclusive_scan(Seg g)
+{
+    g = seg_combine<SIGNED>(seg_dpp<0x111, 0xf, SIGNED>(g), g);
+    g = seg_combine<SIGNED>(seg_dpp<0x112, 0xf, SIGNED>(g), g);
+    g = seg_combine<SIGNED>(seg_dpp<0x114, 0xf, SIGNED>(g), g);
+    g = seg_combine<SIGNED>(seg_dpp<0x118, 0xf, SIGNED>(g), g);
+    return g;
+}
+
+template <bool SIGNED>
+__device__ __forceinline__ Seg seg_readlane(const Seg &g, int lane)
+{
+    Seg r;
+    r.A = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(g.A), lane));
+    r.M = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(g.M), lane));
+    r.sA = SIGNED ? (uint32_t)__builtin_amdgcn_readlane((int)g.sA, lane) : 0u;
+    r.sM = SIGNED ? (uint32_t)__builtin_amdgcn_readlane((int)g.sM, lane) : 0u;
+    return r;
+}
+
 // Exclusive version of an inclusive result: lane i receives lane i-1's value, lane 0 the identity.
 template <bool SIGNED>
 __device__ __forceinline__ Seg wave_shift_up(const Seg &g)
@@ -209,26 +232,44 @@ __device__ __forceinline__ uint32_t readlane_u(uint32_t v, int lane)
 
 // ---- publishing carries between workgroups ------------------------------------------------------------
 //
-// Carries travel through global memory as relaxed agent-scope atomics, which are served at the level
-// of the memory hierarchy all compute dies share, so no cache write-back or invalidate is needed
-// (an agent-scope release/acquire fence would write back / invalidate a whole L2 per tile).  What
-// remains is ordering inside the publishing and the consuming wave.  Publisher: every payload store
-// must have been acknowledged before the flag store is issued -- stores of one wave to different
-// addresses may complete in any order, and a workgroup-scope fence does not wait for them, hence
-// the explicit s_waitcnt.  Consumer: payload loads are issued only after the flag value has come
-// back (the branch on it is a real dependency); the fence keeps the compiler from moving them up.
-__device__ __forceinline__ void order_release()
-{
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-}
-__device__ __forceinline__ void order_acquire() { __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup"); }
+// Carries travel through global memory as 64-bit records {payload: 32 bits, tag: 32 bits} written and
+// read with relaxed agent-scope atomics.  Such accesses are served at the level of the memory
+// hierarchy all compute dies share (no cache write-back or invalidate is needed) and an aligned 64-bit
+// access is indivisible, so a record is its own ready-flag: it is valid for a launch iff its tag
+// carries that launch's epoch.  tag = epoch << 2 | two user bits (signs).  Nothing has to be ordered on
+// the publishing side, nothing has to be cleared between launches (older epochs never match), and a
+// consumer gets flag and payload in one round trip.
+typedef unsigned long long rec_t;
 
-__device__ __forceinline__ void pub_f(float *p, float v) { __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); }
-__device__ __forceinline__ void pub_u(uint32_t *p, uint32_t v) { __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); }
-__device__ __forceinline__ void pub_d(double *p, double v) { __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); }
-__device__ __forceinline__ float get_f(const float *p) { return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); }
-__device__ __forceinline__ uint32_t get_u(const uint32_t *p) { return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); }
-__device__ __forceinline__ double get_d(const double *p) { return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); }
+__device__ __forceinline__ void rec_put(rec_t *p, uint32_t payload, uint32_t epoch, uint32_t bits)
+{
+    const rec_t v = ((rec_t)((epoch << 2) | (bits & 3u)) << 32) | payload;
+    __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ rec_t rec_get(const rec_t *p)
+{
+    return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ bool rec_ok(rec_t r, uint32_t epoch) { return ((uint32_t)(r >> 34)) == (epoch & 0x3fffffffu); }
+__device__ __forceinline__ uint32_t rec_payload(rec_t r) { return (uint32_t)r; }
+__device__ __forceinline__ uint32_t rec_bits(rec_t r) { return (uint32_t)(r >> 32) & 3u; }
+
+// A segment summary is two records: {A, tag | sA, sM} and {M, tag}.
+template <bool SIGNED>
+__device__ __forceinline__ void seg_put(rec_t *pa, rec_t *pm, const Seg &g, uint32_t epoch)
+{
+    rec_put(pa, f2u(g.A), epoch, SIGNED ? ((g.sA >> 31) | ((g.sM >> 31) << 1)) : 0u);
+    rec_put(pm, f2u(g.M), epoch, 0u);
+}
+template <bool SIGNED>
+__device__ __forceinline__ Seg seg_from(rec_t ra, rec_t rm)
+{
+    Seg g;
+    g.A = u2f(rec_payload(ra));
+    g.M = u2f(rec_payload(rm));
+    g.sA = SIGNED ? (rec_bits(ra) << 31) : 0u;
+    g.sM = SIGNED ? (rec_bits(ra) << 30) : 0u;
+    return g;
+}
 
 } // namespace hs

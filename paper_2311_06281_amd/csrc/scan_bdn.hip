@@ -262,12 +262,18 @@ __global__ __launch_bounds__(256, VECIO ? 4 : 1) void heinsen_scan_rows_wave(Row
 }
 
 // ---- tiles with a chained carry ------------------------------------------------------------------------
+//
+// Tile index c inside a row is read in base 16: c = ((s*16 + q)*16 + g)*16 + r.  Summaries are published
+// at three levels -- a tile's own (level 1), the 16 tiles of a group folded by its last tile (level 2),
+// the 16 groups of a block folded by the block's last tile (level 3) -- and the state at the start of
+// every 4096-tile super-block s, in float64, by the last tile of the previous one.  A tile therefore
+// reads at most 15 + 15 + 15 summaries and one state, all in one round of loads (one per lane of wave
+// 0), and folds them in a fixed order: results do not depend on timing.  Only the super-block states
+// form a chain, n / (4096 * tile) links long.
 
-constexpr int kTileWaves = 4;   // waves per workgroup
+constexpr int kTileWaves = 8;   // waves per workgroup
 constexpr int kTileItems = 16;  // elements per lane
 constexpr int kTile = kTileWaves * 64 * kTileItems;
-constexpr int kPerLane = 4;     // earlier tiles of the group folded by one lane of wave 0
-constexpr int kGroupK = 64 * kPerLane;
 
 struct TileParams {
     const void *a;
@@ -276,17 +282,12 @@ struct TileParams {
     float *out;
     int64_t rows, n;
     int x0_stride;
-    uint32_t tpr;       // tiles per row
-    uint32_t gpr;       // groups per row
-    uint32_t ntiles;    // rows * tpr
-    uint32_t *counters; // [0] ticket
-    uint32_t *agg_flag; // [ntiles]
-    uint32_t *st_flag;  // [rows * gpr]
-    float *agg_A;       // [ntiles]
-    float *agg_M;
-    uint32_t *agg_S;
-    double *st_L;       // [rows * gpr] log2|x| at the start of a group, float64
-    uint32_t *st_S;
+    uint32_t tpr;          // tiles per row
+    uint32_t epoch;
+    uint32_t ticket_base;
+    rec_t *ticket;
+    rec_t *recs;           // per row: level-1, level-2, level-3 summaries (2 records each), states (2 records each)
+    uint32_t off2, off3, off4, row_stride; // record offsets of levels 2, 3 and the states inside a row's block
 };
 
 struct State64 {
@@ -295,7 +296,7 @@ struct State64 {
 };
 
 // seg_apply with the state kept in float64: only the (small) correction log2(1 +- 2^-|t|) is formed in
-// float32, so a long chain of groups does not accumulate float32 rounding of the state itself.
+// float32, so a long chain does not accumulate float32 rounding of the state itself.
 template <bool SIGNED>
 __device__ __forceinline__ State64 seg_apply64(const State64 &x, const Seg &g)
 {
@@ -328,17 +329,14 @@ __global__ __launch_bounds__(kTileWaves * 64) void heinsen_scan_tiles(TileParams
     __shared__ uint32_t lds_startS;
 
     const int lane = threadIdx.x & 63;
-    const int w = threadIdx.x >> 6;
+    const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
 
     uint32_t tile = blockIdx.x;
     if (MULTI) {
         // tickets: a tile only ever waits for tiles with smaller tickets, which are already running
-        // whoever draws the last ticket puts the counter back to zero for the next launch
-        if (threadIdx.x == 0) {
-            const uint32_t tk = atomicAdd(&p.counters[0], 1u);
-            if (tk == p.ntiles - 1u) pub_u(&p.counters[0], 0u);
-            s_tile = tk;
-        }
+        if (threadIdx.x == 0)
+            s_tile = __hip_atomic_fetch_add(reinterpret_cast<uint32_t *>(p.ticket), 1u, __ATOMIC_RELAXED,
+                                            __HIP_MEMORY_SCOPE_AGENT) - p.ticket_base;
         __syncthreads();
         tile = __builtin_amdgcn_readfirstlane(s_tile);
     }
@@ -347,6 +345,32 @@ __global__ __launch_bounds__(kTileWaves * 64) void heinsen_scan_tiles(TileParams
     const InT *arow = reinterpret_cast<const InT *>(p.a) + row * p.n;
     const InT *brow = reinterpret_cast<const InT *>(p.b) + row * p.n;
     const int64_t start = (int64_t)c * kTile + (int64_t)threadIdx.x * ITEMS;
+
+    // ---- wave 0 asks for the carry records it needs before the tile's own loads (see scan_bnd.hip) ---
+    const uint32_t r = c & 15u, g = (c >> 4) & 15u, q = (c >> 8) & 15u, sb = c >> 12;
+    const bool more = c + 1 < p.tpr;
+    rec_t *const rrow = p.recs + (size_t)row * p.row_stride;
+    rec_t ra = 0, rm = 0;
+    const rec_t *fp = nullptr;
+    bool need = false;
+    if (MULTI && w == 0) {
+        const int sub = lane & 15, lvl = lane >> 4; // lanes 0-15: level 3, 16-31: level 2, 32-47: level 1
+        if (lvl == 0 && (uint32_t)sub < q) { need = true; fp = rrow + p.off3 + 2 * (size_t)(((c >> 12) << 4) + sub); }
+        if (lvl == 1 && (uint32_t)sub < g) { need = true; fp = rrow + p.off2 + 2 * (size_t)(((c >> 8) << 4) + sub); }
+        if (lvl == 2 && (uint32_t)sub < r) { need = true; fp = rrow + 2 * (size_t)(((c >> 4) << 4) + sub); }
+        if (lane == 63 && sb > 0) { need = true; fp = rrow + p.off4 + 2 * (size_t)sb; }
+    }
+    auto fetch_records = [&]() -> bool {
+        bool ok = true;
+        if (need) {
+            ra = rec_get(fp);
+            rm = rec_get(fp + 1);
+            ok = rec_ok(ra, p.epoch) && rec_ok(rm, p.epoch);
+        }
+        return __builtin_amdgcn_ballot_w64(!ok) == 0ull;
+    };
+    bool have_records = false;
+    if (MULTI && w == 0) have_records = fetch_records();
 
     float Av[ITEMS], Mv[ITEMS];
     uint32_t sw;
@@ -377,82 +401,51 @@ __global__ __launch_bounds__(kTileWaves * 64) void heinsen_scan_tiles(TileParams
 
     if (w == 0) {
         State64 st;
-        if (!MULTI) {
+        {
             float lx;
             encode<SIGNED, LOG_IN>(p.x0[p.x0_stride ? row : 0], lx, st.s);
             st.lx = (double)lx;
-        } else {
-            const uint32_t g = c / kGroupK;
-            const uint32_t r = c % kGroupK;
-            const bool more = c + 1 < p.tpr;
-            if (more && r < kGroupK - 1) {
-                if (lane == 0) {
-                    pub_f(&p.agg_A[tile], total.A);
-                    pub_f(&p.agg_M[tile], total.M);
-                    pub_u(&p.agg_S[tile], (total.sA >> 31) | ((total.sM >> 31) << 1));
-                }
-                order_release();
-                // A flag holds the number of tiles that will still read the record; each reader takes
-                // one off after its read, so the flag is back at zero when the kernel ends.
-                const uint32_t last_in_group = min(g * kGroupK + kGroupK - 1, p.tpr - 1);
-                if (lane == 0) pub_u(&p.agg_flag[tile], last_in_group - c);
+        }
+        if (MULTI) {
+            if (more && r < 15u && lane == 0) seg_put<SIGNED>(rrow + 2 * (size_t)c, rrow + 2 * (size_t)c + 1, total, p.epoch);
+            if (!have_records) {
+                while (!fetch_records()) __builtin_amdgcn_s_sleep(2);
             }
-            // lane i folds the summaries of tiles first + i*kPerLane .. + kPerLane - 1 that precede c
-            const uint32_t first = tile - r; // first tile of the group (same row)
-            {
-#pragma unroll
-                for (int j = 0; j < kPerLane; ++j) {
-                    const uint32_t rr = (uint32_t)lane * kPerLane + j;
-                    if (rr < r) {
-                        while (get_u(&p.agg_flag[first + rr]) == 0u) __builtin_amdgcn_s_sleep(2);
-                        (void)__hip_atomic_fetch_sub(&p.agg_flag[first + rr], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            // folds of the three levels, each in index order inside its row of 16 lanes
+            Seg part = (need && lane < 48) ? seg_from<SIGNED>(ra, rm) : seg_identity();
+            part = row16_inclusive_scan<SIGNED>(part);
+            const Seg f3 = seg_readlane<SIGNED>(part, 15);
+            const Seg f2 = seg_readlane<SIGNED>(part, 31);
+            const Seg f1 = seg_readlane<SIGNED>(part, 47);
+            if (sb > 0) {
+                // lane 63 holds the super-block state: payloads are the high and low word of the double,
+                // the sign rides in the user bits of the first record
+                const uint32_t hi = (uint32_t)__builtin_amdgcn_readlane((int)rec_payload(ra), 63);
+                const uint32_t lo = (uint32_t)__builtin_amdgcn_readlane((int)rec_payload(rm), 63);
+                const uint32_t sg = (uint32_t)__builtin_amdgcn_readlane((int)rec_bits(ra), 63);
+                st.lx = __longlong_as_double((long long)(((unsigned long long)hi << 32) | lo));
+                st.s = SIGNED ? (sg << 31) : 0u;
+            }
+            const State64 st3 = seg_apply64<SIGNED>(st, f3); // state at the start of the 256-tile block
+            if (more && r == 15u) {
+                const Seg a2 = seg_combine<SIGNED>(f1, total); // this group of 16 tiles
+                if (g < 15u) {
+                    if (lane == 0) seg_put<SIGNED>(rrow + p.off2 + 2 * (size_t)(c >> 4), rrow + p.off2 + 2 * (size_t)(c >> 4) + 1, a2, p.epoch);
+                } else {
+                    const Seg a3 = seg_combine<SIGNED>(f2, a2); // this block of 256 tiles
+                    if (q < 15u) {
+                        if (lane == 0) seg_put<SIGNED>(rrow + p.off3 + 2 * (size_t)(c >> 8), rrow + p.off3 + 2 * (size_t)(c >> 8) + 1, a3, p.epoch);
+                    } else {
+                        const State64 nx = seg_apply64<SIGNED>(st3, a3); // start of the next super-block
+                        const unsigned long long bits = (unsigned long long)__double_as_longlong(nx.lx);
+                        if (lane == 0) {
+                            rec_put(rrow + p.off4 + 2 * (size_t)(sb + 1), (uint32_t)(bits >> 32), p.epoch, SIGNED ? (nx.s >> 31) : 0u);
+                            rec_put(rrow + p.off4 + 2 * (size_t)(sb + 1) + 1, (uint32_t)bits, p.epoch, 0u);
+                        }
                     }
                 }
-                if (g > 0 && lane == 63) {
-                    while (get_u(&p.st_flag[row * p.gpr + g]) == 0u) __builtin_amdgcn_s_sleep(2);
-                    (void)__hip_atomic_fetch_sub(&p.st_flag[row * p.gpr + g], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                }
-                order_acquire();
             }
-            Seg part = seg_identity();
-#pragma unroll
-            for (int j = 0; j < kPerLane; ++j) {
-                const uint32_t rr = (uint32_t)lane * kPerLane + j;
-                Seg h = seg_identity();
-                if (rr < r) {
-                    h.A = get_f(&p.agg_A[first + rr]);
-                    h.M = get_f(&p.agg_M[first + rr]);
-                    const uint32_t s = SIGNED ? get_u(&p.agg_S[first + rr]) : 0u;
-                    h.sA = s << 31;
-                    h.sM = s << 30;
-                }
-                part = (j == 0) ? h : seg_combine<SIGNED>(part, h);
-            }
-            Seg fold = wave_inclusive_scan<SIGNED>(part);
-            fold.A = readlane_f(fold.A, 63);
-            fold.M = readlane_f(fold.M, 63);
-            fold.sA = readlane_u(fold.sA, 63);
-            fold.sM = readlane_u(fold.sM, 63);
-
-            if (g == 0) {
-                float lx;
-                encode<SIGNED, LOG_IN>(p.x0[p.x0_stride ? row : 0], lx, st.s);
-                st.lx = (double)lx;
-            } else {
-                st.lx = get_d(&p.st_L[row * p.gpr + g]);
-                st.s = SIGNED ? get_u(&p.st_S[row * p.gpr + g]) : 0u;
-            }
-            if (r > 0) st = seg_apply64<SIGNED>(st, fold);
-            if (more && r == kGroupK - 1) {
-                State64 nx = seg_apply64<SIGNED>(st, total);
-                if (lane == 0) {
-                    pub_d(&p.st_L[row * p.gpr + g + 1], nx.lx);
-                    pub_u(&p.st_S[row * p.gpr + g + 1], nx.s);
-                }
-                order_release();
-                const uint32_t next_group_tiles = min((uint32_t)kGroupK, p.tpr - (g + 1) * kGroupK);
-                if (lane == 0) pub_u(&p.st_flag[row * p.gpr + g + 1], next_group_tiles);
-            }
+            st = seg_apply64<SIGNED>(seg_apply64<SIGNED>(st3, f2), f1);
         }
         if (lane == 0) {
             lds_startL = (float)st.lx;
@@ -466,7 +459,6 @@ __global__ __launch_bounds__(kTileWaves * 64) void heinsen_scan_tiles(TileParams
     st.s = lds_startS;
     st = seg_apply<SIGNED>(st, seg_combine<SIGNED>(wave_excl, lane_excl));
     lane_emit<SIGNED, LOG_OUT, ITEMS, VECIO>(p.out + row * p.n, start, p.n, st, Av, Mv, sw);
-
 }
 
 // ---- host side -------------------------------------------------------------------------------------------
@@ -479,9 +471,9 @@ struct BdnPlan {
     bool vecio;
     bool multi;
     int64_t rows;
-    uint32_t tpr, gpr, ntiles;
-    size_t off_agg_flag, off_st_flag, flag_bytes;
-    size_t off_agg_A, off_agg_M, off_agg_S, off_st_L, off_st_S, data_bytes;
+    uint32_t tpr, ntiles;
+    uint32_t off2, off3, off4, row_stride;
+    size_t records;
 };
 
 BdnPlan make_plan(const ScanCall &c)
@@ -490,37 +482,27 @@ BdnPlan make_plan(const ScanCall &c)
     pl.rows = c.B * c.D;
     const int64_t vl = c.bf16 ? 8 : 4;
     auto aligned16 = [](const void *ptr) { return (reinterpret_cast<uintptr_t>(ptr) % 16) == 0; };
-    pl.vecio = aligned16(c.a) && aligned16(c.b) && aligned16(c.out) && (pl.rows == 1 || c.n % vl == 0) &&
-               (c.n % vl == 0);
+    pl.vecio = aligned16(c.a) && aligned16(c.b) && aligned16(c.out) && (c.n % vl == 0);
     pl.wave_kernel = c.n <= kRowsWaveMax && !(pl.rows < 64 && c.n > 512);
     if (pl.wave_kernel) {
         pl.items = c.n > 1024 ? 32 : (c.n > 512 ? 16 : 8);
         return pl;
     }
     pl.tpr = (uint32_t)ceil_div(c.n, kTile);
-    pl.gpr = (uint32_t)ceil_div(pl.tpr, kGroupK);
     pl.ntiles = (uint32_t)(pl.rows * pl.tpr);
     pl.multi = pl.tpr > 1;
     if (!pl.multi) return pl;
-    size_t off = 64;
-    pl.off_agg_flag = off;
-    off += (size_t)pl.ntiles * 4;
-    pl.off_st_flag = off;
-    off += (size_t)pl.rows * pl.gpr * 4;
-    pl.flag_bytes = align_up(off, 256);
-    off = 0;
-    const size_t agg = align_up((size_t)pl.ntiles * 4, 256);
-    pl.off_agg_A = off; off += agg;
-    pl.off_agg_M = off; off += agg;
-    pl.off_agg_S = off; off += agg;
-    pl.off_st_L = off; off += align_up((size_t)pl.rows * pl.gpr * 8, 256);
-    pl.off_st_S = off; off += align_up((size_t)pl.rows * pl.gpr * 4, 256);
-    pl.data_bytes = off;
+    const uint32_t n1 = pl.tpr, n2 = (pl.tpr + 15) / 16, n3 = (pl.tpr + 255) / 256, n4 = (pl.tpr + 4095) / 4096 + 1;
+    pl.off2 = 2 * n1;
+    pl.off3 = pl.off2 + 2 * n2;
+    pl.off4 = pl.off3 + 2 * n3;
+    pl.row_stride = pl.off4 + 2 * n4;
+    pl.records = (size_t)pl.rows * pl.row_stride;
     return pl;
 }
 
 template <bool SIGNED, bool LOG_IN, bool LOG_OUT, typename InT>
-hipError_t launch_mode(const ScanCall &c, const BdnPlan &pl, char *flags, char *data)
+hipError_t launch_mode(const ScanCall &c, const BdnPlan &pl, rec_t *records, LaunchTag tag)
 {
     if (pl.wave_kernel) {
         RowsParams p;
@@ -556,16 +538,14 @@ hipError_t launch_mode(const ScanCall &c, const BdnPlan &pl, char *flags, char *
     p.n = c.n;
     p.x0_stride = c.x0_scalar ? 0 : 1;
     p.tpr = pl.tpr;
-    p.gpr = pl.gpr;
-    p.ntiles = pl.ntiles;
-    p.counters = reinterpret_cast<uint32_t *>(flags);
-    p.agg_flag = reinterpret_cast<uint32_t *>(flags + pl.off_agg_flag);
-    p.st_flag = reinterpret_cast<uint32_t *>(flags + pl.off_st_flag);
-    p.agg_A = reinterpret_cast<float *>(data + pl.off_agg_A);
-    p.agg_M = reinterpret_cast<float *>(data + pl.off_agg_M);
-    p.agg_S = reinterpret_cast<uint32_t *>(data + pl.off_agg_S);
-    p.st_L = reinterpret_cast<double *>(data + pl.off_st_L);
-    p.st_S = reinterpret_cast<uint32_t *>(data + pl.off_st_S);
+    p.epoch = tag.epoch;
+    p.ticket_base = tag.ticket_base;
+    p.ticket = records;
+    p.recs = records ? records + kRecordBase : nullptr;
+    p.off2 = pl.off2;
+    p.off3 = pl.off3;
+    p.off4 = pl.off4;
+    p.row_stride = pl.row_stride;
     dim3 grid(pl.ntiles), block(kTileWaves * 64);
 #define HS_TILES(VEC_, MULTI_) \
     hipLaunchKernelGGL((heinsen_scan_tiles<SIGNED, LOG_IN, LOG_OUT, InT, VEC_, MULTI_>), grid, block, 0, c.stream, p)
@@ -580,9 +560,9 @@ hipError_t launch_mode(const ScanCall &c, const BdnPlan &pl, char *flags, char *
     return hipGetLastError();
 }
 
-hipError_t launch_dispatch(const ScanCall &c, const BdnPlan &pl, char *flags, char *data)
+hipError_t launch_dispatch(const ScanCall &c, const BdnPlan &pl, rec_t *records, LaunchTag tag)
 {
-    HS_DISPATCH_MODE(c, launch_mode, c, pl, flags, data);
+    HS_DISPATCH_MODE(c, launch_mode, c, pl, records, tag);
 }
 
 } // namespace
@@ -590,13 +570,13 @@ hipError_t launch_dispatch(const ScanCall &c, const BdnPlan &pl, char *flags, ch
 ScratchNeed bdn_scratch(const ScanCall &c)
 {
     BdnPlan pl = make_plan(c);
-    return ScratchNeed{pl.flag_bytes, pl.data_bytes};
+    return ScratchNeed{pl.records, pl.multi ? pl.ntiles : 0u};
 }
 
-hipError_t bdn_launch(const ScanCall &c, void *flags, void *data)
+hipError_t bdn_launch(const ScanCall &c, unsigned long long *records, LaunchTag tag)
 {
     BdnPlan pl = make_plan(c);
-    return launch_dispatch(c, pl, static_cast<char *>(flags), static_cast<char *>(data));
+    return launch_dispatch(c, pl, records, tag);
 }
 
 const char *bdn_kernel_name(const ScanCall &c)

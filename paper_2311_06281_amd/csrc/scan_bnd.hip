@@ -2,10 +2,10 @@
 //
 // A workgroup of NW waves owns CH = 64*VEC adjacent channels for NW*T consecutive time steps ("tile").
 // Wave w of the workgroup scans steps [w*T, (w+1)*T) of the tile serially in each lane (one lane = VEC
-// channels, loads and stores coalesced across lanes), keeping the T local segment summaries in
-// registers.  Summaries of the waves are chained through LDS, summaries of the tiles of one channel
-// column through global memory: tiles are grouped G at a time along the time axis, a tile folds the
-// published summaries of the earlier tiles of its group (always in the same order, so results are
+// channels, loads and stores coalesced across lanes), keeping the T per-element records in registers.
+// Summaries of the waves are chained through LDS, summaries of the tiles of one channel column through
+// global memory: tiles are grouped G at a time along the time axis, a tile folds the published
+// summaries of the earlier tiles of its group (always in the same order, so results are
 // bit-reproducible) onto the state at the start of the group, and the last tile of a group publishes
 // the state at the start of the next.  Every element is read once and written once.
 //
@@ -18,26 +18,21 @@
 namespace hs {
 namespace {
 
-
 struct BndParams {
     const void *a;
     const void *b;
     const float *x0;
     float *out;
     int64_t D, n;
-    int x0_stride;     // 0: one x0 for all, 1: x0[b*D + d]
-    int cols_per_b;    // ceil(D / CH)
-    int ncols;         // B * cols_per_b
-    int nchunks;       // ceil(n / (NW*T))
-    uint32_t ntiles;   // ncols * nchunks
-    uint32_t *counters; // [0] ticket
-    uint32_t *agg_flag; // [ntiles]
-    uint32_t *st_flag;  // [ngroups * ncols]
-    float *agg_A;       // [ntiles * CH]
-    float *agg_M;
-    uint32_t *agg_S;    // bit0: sign of 2^A factor, bit1: sign of 2^M term
-    float *st_L;        // [ngroups * ncols * CH] state at the start of a group
-    uint32_t *st_S;
+    int x0_stride;    // 0: one x0 for all, 1: x0[b*D + d]
+    int cols_per_b;   // ceil(D / CH)
+    int ncols;        // B * cols_per_b
+    int nchunks;      // ceil(n / (NW*T))
+    uint32_t epoch;
+    uint32_t ticket_base;
+    rec_t *ticket;    // word 0 of the record buffer
+    rec_t *agg;       // [ntiles][2][CH]  tile summaries: plane 0 = {A | signs}, plane 1 = {M}
+    rec_t *state;     // [ngroups][ncols][CH] state at the start of a group: {log2|x| | sign}
 #ifdef HS_TRACE
     unsigned long long *trace; // [ntiles][8] wall-clock stamps of wave 0 (100 MHz), development only
 #endif
@@ -92,8 +87,8 @@ __device__ __forceinline__ void unpack_signs(uint32_t s, Seg &g)
 template <bool SIGNED, bool LOG_IN, bool LOG_OUT, typename InT, int VEC, int T, int NW, int G, int MINW, bool SB>
 __global__ __launch_bounds__(NW * 64, MINW) void heinsen_scan_bnd(BndParams p)
 {
-    constexpr int kGroup = G;
     constexpr int CH = 64 * VEC;
+    constexpr int GP = G > 1 ? G - 1 : 1;
     static_assert(T <= 32, "one sign word per channel");
     __shared__ uint32_t s_tile;
     __shared__ float lds_A[NW][CH];
@@ -107,12 +102,9 @@ __global__ __launch_bounds__(NW * 64, MINW) void heinsen_scan_bnd(BndParams p)
 
     // Tiles are handed out in start order, so every tile a workgroup may wait for (same column,
     // earlier chunk => smaller ticket) belongs to a workgroup that is already running.
-    // Whoever draws the last ticket puts the counter back to zero for the next launch.
-    if (threadIdx.x == 0) {
-        const uint32_t tk = atomicAdd(&p.counters[0], 1u);
-        if (tk == p.ntiles - 1u) pub_u(&p.counters[0], 0u);
-        s_tile = tk;
-    }
+    if (threadIdx.x == 0)
+        s_tile = __hip_atomic_fetch_add(reinterpret_cast<uint32_t *>(p.ticket), 1u, __ATOMIC_RELAXED,
+                                        __HIP_MEMORY_SCOPE_AGENT) - p.ticket_base;
     __syncthreads();
     const uint32_t tile = __builtin_amdgcn_readfirstlane(s_tile);
     HS_STAMP(0);
@@ -120,8 +112,11 @@ __global__ __launch_bounds__(NW * 64, MINW) void heinsen_scan_bnd(BndParams p)
     const int col = (int)(tile % (uint32_t)p.ncols);
     const int bidx = col / p.cols_per_b;
     const int cg = col % p.cols_per_b;
+    const int g = chunk / G;
+    const int r = chunk % G;
+    const bool more = chunk + 1 < p.nchunks;
 
-    const int loff = lane * VEC;                       // the only per-lane part of every address
+    const int loff = lane * VEC; // the only per-lane part of every address
     const int64_t d0 = (int64_t)cg * CH + loff;
     const bool chan_ok = d0 < p.D; // D is a multiple of VEC, so the whole vector is in range
     const int64_t t0 = (int64_t)chunk * (NW * T) + (int64_t)w * T;
@@ -129,22 +124,40 @@ __global__ __launch_bounds__(NW * 64, MINW) void heinsen_scan_bnd(BndParams p)
     const InT *ap = reinterpret_cast<const InT *>(p.a) + ubase;
     const InT *bp = reinterpret_cast<const InT *>(p.b) + ubase;
 
-    // ---- wave 0 looks at the flags of the records it will need before anything else is in flight: if
-    //      the earlier tiles of the group have already published (the usual case once the kernel is past
-    //      its first round), the records are fetched behind the tile's own loads and cost no latency ----
-    const int g = chunk / kGroup;
-    const int r = chunk % kGroup;
-    const bool more = chunk + 1 < p.nchunks;
-    const bool need_agg = (w == 0) && (lane < r);
-    const bool need_st = (w == 0) && (lane == 63) && (g > 0);
-    uint32_t *const fp = need_agg ? &p.agg_flag[(size_t)(g * kGroup + lane) * p.ncols + col]
-                                  : &p.st_flag[(size_t)g * p.ncols + col];
-    uint32_t early_flag = 1u;
-    if (need_agg || need_st) early_flag = get_u(fp);
+    // ---- wave 0 asks for the carry records it will need before anything else is in flight: once the
+    //      kernel is past its first round the earlier tiles of the group have usually published, and the
+    //      records then arrive ahead of the tile's own loads at no cost in latency --------------------
+    rec_t rA[GP][VEC], rM[GP][VEC], rS[VEC];
+    auto fetch_records = [&]() -> bool {
+        bool ok = true;
+        if (g > 0) {
+            const rec_t *sp = p.state + ((size_t)g * p.ncols + col) * CH + loff;
+#pragma unroll
+            for (int v = 0; v < VEC; ++v) {
+                rS[v] = rec_get(sp + v);
+                ok = ok && rec_ok(rS[v], p.epoch);
+            }
+        }
+#pragma unroll
+        for (int j = 0; j < G - 1; ++j) {
+            if (j < r) {
+                const rec_t *tp = p.agg + ((size_t)(g * G + j) * p.ncols + col) * (2 * CH) + loff;
+#pragma unroll
+                for (int v = 0; v < VEC; ++v) {
+                    rA[j][v] = rec_get(tp + v);
+                    rM[j][v] = rec_get(tp + CH + v);
+                    ok = ok && rec_ok(rA[j][v], p.epoch) && rec_ok(rM[j][v], p.epoch);
+                }
+            }
+        }
+        return __builtin_amdgcn_ballot_w64(!ok) == 0ull;
+    };
+    bool have_records = false;
+    if (w == 0) have_records = fetch_records();
 
     // ---- load: the lane's T x VEC inputs -------------------------------------------------------
     float Av[T][VEC], Mv[T][VEC];
-    const float id_a = LOG_IN ? 0.0f : 1.0f;       // a = 1, b = 0 leave the state unchanged
+    const float id_a = LOG_IN ? 0.0f : 1.0f; // a = 1, b = 0 leave the state unchanged
     const float id_b = LOG_IN ? -INFINITY : 0.0f;
     if (chan_ok && t0 + T <= p.n) {
 #pragma unroll
@@ -166,36 +179,6 @@ __global__ __launch_bounds__(NW * 64, MINW) void heinsen_scan_bnd(BndParams p)
                 }
             }
         }
-    }
-
-    float fA[kGroup > 1 ? kGroup - 1 : 1][VEC], fM[kGroup > 1 ? kGroup - 1 : 1][VEC], gL[VEC];
-    uint32_t fS[kGroup > 1 ? kGroup - 1 : 1][VEC], gS[VEC];
-    bool have_records = false;
-    auto fetch_records = [&]() {
-        if (g > 0) {
-            const size_t si = ((size_t)g * p.ncols + col) * CH + (size_t)lane * VEC;
-#pragma unroll
-            for (int v = 0; v < VEC; ++v) {
-                gL[v] = get_f(&p.st_L[si + v]);
-                gS[v] = SIGNED ? get_u(&p.st_S[si + v]) : 0u;
-            }
-        }
-#pragma unroll
-        for (int j = 0; j < kGroup - 1; ++j) {
-            if (j < r) {
-                const size_t ti = ((size_t)(g * kGroup + j) * p.ncols + col) * CH + (size_t)lane * VEC;
-#pragma unroll
-                for (int v = 0; v < VEC; ++v) {
-                    fA[j][v] = get_f(&p.agg_A[ti + v]);
-                    fM[j][v] = get_f(&p.agg_M[ti + v]);
-                    fS[j][v] = SIGNED ? get_u(&p.agg_S[ti + v]) : 0u;
-                }
-            }
-        }
-    };
-    if (w == 0) {
-        have_records = __builtin_amdgcn_ballot_w64(early_flag == 0u) == 0ull;
-        if (have_records) fetch_records(); // issued after the flags were seen set: a real dependency
     }
 
     // ---- encode + serial scan in each lane; Av/Mv become the per-element records (see stash) --------
@@ -228,9 +211,9 @@ __global__ __launch_bounds__(NW * 64, MINW) void heinsen_scan_bnd(BndParams p)
     // ---- chain the waves of the workgroup through LDS ------------------------------------------
 #pragma unroll
     for (int v = 0; v < VEC; ++v) {
-        lds_A[w][lane * VEC + v] = run[v].A;
-        lds_M[w][lane * VEC + v] = run[v].M;
-        if (SIGNED) lds_S[w][lane * VEC + v] = pack_signs(run[v]);
+        lds_A[w][loff + v] = run[v].A;
+        lds_M[w][loff + v] = run[v].M;
+        if (SIGNED) lds_S[w][loff + v] = pack_signs(run[v]);
     }
     __syncthreads();
 
@@ -241,101 +224,70 @@ __global__ __launch_bounds__(NW * 64, MINW) void heinsen_scan_bnd(BndParams p)
         const int cnt = (w == 0) ? NW : w;
 #pragma unroll
         for (int v = 0; v < VEC; ++v) {
-            Seg g;
-            g.A = lds_A[0][lane * VEC + v];
-            g.M = lds_M[0][lane * VEC + v];
-            g.sA = g.sM = 0u;
-            if (SIGNED) unpack_signs(lds_S[0][lane * VEC + v], g);
+            Seg acc;
+            acc.A = lds_A[0][loff + v];
+            acc.M = lds_M[0][loff + v];
+            acc.sA = acc.sM = 0u;
+            if (SIGNED) unpack_signs(lds_S[0][loff + v], acc);
             for (int j = 1; j < cnt; ++j) {
                 Seg h;
-                h.A = lds_A[j][lane * VEC + v];
-                h.M = lds_M[j][lane * VEC + v];
+                h.A = lds_A[j][loff + v];
+                h.M = lds_M[j][loff + v];
                 h.sA = h.sM = 0u;
-                if (SIGNED) unpack_signs(lds_S[j][lane * VEC + v], h);
-                g = seg_combine<SIGNED>(g, h);
+                if (SIGNED) unpack_signs(lds_S[j][loff + v], h);
+                acc = seg_combine<SIGNED>(acc, h);
             }
-            pre[v] = g;
+            pre[v] = acc;
         }
     }
 
     // ---- wave 0: publish the tile summary, obtain the state at the start of the tile -------------
     if (w == 0) {
         HS_STAMP(2);
-        const size_t my = (size_t)tile * CH + (size_t)lane * VEC;
-        if (more && r < kGroup - 1) {
+        if (more && r < G - 1) {
+            rec_t *tp = p.agg + (size_t)tile * (2 * CH) + loff;
 #pragma unroll
-            for (int v = 0; v < VEC; ++v) {
-                pub_f(&p.agg_A[my + v], pre[v].A);
-                pub_f(&p.agg_M[my + v], pre[v].M);
-                if (SIGNED) pub_u(&p.agg_S[my + v], pack_signs(pre[v]));
-            }
-            order_release();
-            // A flag holds the number of tiles that will still read the record; each reader takes one
-            // off after its read, so the flag is back at zero when the kernel ends.
-            const int last_in_group = min(g * kGroup + kGroup - 1, p.nchunks - 1);
-            if (lane == 0) pub_u(&p.agg_flag[tile], (uint32_t)(last_in_group - chunk));
+            for (int v = 0; v < VEC; ++v) seg_put<SIGNED>(tp + v, tp + CH + v, pre[v], p.epoch);
         }
-
         HS_STAMP(3);
         if (!have_records) {
-            // wait for the r earlier tiles of the group (lanes 0..r-1) and for the group's start state
-            // (lane 63), all polls in flight together
-            if (need_agg || need_st) {
-                while (get_u(fp) == 0u) __builtin_amdgcn_s_sleep(2);
-            }
-            order_acquire();
-            fetch_records();
+            while (!fetch_records()) __builtin_amdgcn_s_sleep(2);
         }
-
         HS_STAMP(4);
         State st[VEC];
-        if (g == 0) {
 #pragma unroll
-            for (int v = 0; v < VEC; ++v) {
+        for (int v = 0; v < VEC; ++v) {
+            if (g == 0) {
                 float x0v = LOG_IN ? 0.0f : 1.0f;
                 if (chan_ok) x0v = p.x0[p.x0_stride ? ((int64_t)bidx * p.D + d0 + v) : 0];
                 encode<SIGNED, LOG_IN>(x0v, st[v].lx, st[v].s);
-            }
-        } else {
-#pragma unroll
-            for (int v = 0; v < VEC; ++v) {
-                st[v].lx = gL[v];
-                st[v].s = gS[v];
+            } else {
+                st[v].lx = u2f(rec_payload(rS[v]));
+                st[v].s = SIGNED ? (rec_bits(rS[v]) << 31) : 0u;
             }
         }
         // fold the earlier tiles of the group in tile order
 #pragma unroll
-        for (int j = 0; j < kGroup - 1; ++j) {
+        for (int j = 0; j < G - 1; ++j) {
             if (j < r) {
 #pragma unroll
-                for (int v = 0; v < VEC; ++v) {
-                    Seg h;
-                    h.A = fA[j][v];
-                    h.M = fM[j][v];
-                    h.sA = h.sM = 0u;
-                    if (SIGNED) unpack_signs(fS[j][v], h);
-                    st[v] = seg_apply<SIGNED>(st[v], h);
-                }
+                for (int v = 0; v < VEC; ++v) st[v] = seg_apply<SIGNED>(st[v], seg_from<SIGNED>(rA[j][v], rM[j][v]));
             }
         }
 #pragma unroll
         for (int v = 0; v < VEC; ++v) {
-            lds_startL[lane * VEC + v] = st[v].lx;
-            lds_startS[lane * VEC + v] = st[v].s;
+            lds_startL[loff + v] = st[v].lx;
+            lds_startS[loff + v] = st[v].s;
         }
         HS_STAMP(5);
         // last tile of a group: the state after this tile starts the next group
-        if (more && r == kGroup - 1) {
-            const size_t si = ((size_t)(g + 1) * p.ncols + col) * CH + (size_t)lane * VEC;
+        if (more && r == G - 1) {
+            rec_t *sp = p.state + ((size_t)(g + 1) * p.ncols + col) * CH + loff;
 #pragma unroll
             for (int v = 0; v < VEC; ++v) {
                 State nx = seg_apply<SIGNED>(st[v], pre[v]);
-                pub_f(&p.st_L[si + v], nx.lx);
-                if (SIGNED) pub_u(&p.st_S[si + v], nx.s);
+                rec_put(sp + v, f2u(nx.lx), p.epoch, SIGNED ? (nx.s >> 31) : 0u);
             }
-            order_release();
-            const int next_group_tiles = min(kGroup, p.nchunks - (g + 1) * kGroup);
-            if (lane == 0) pub_u(&p.st_flag[(size_t)(g + 1) * p.ncols + col], (uint32_t)next_group_tiles);
         }
     }
     __syncthreads();
@@ -345,8 +297,8 @@ __global__ __launch_bounds__(NW * 64, MINW) void heinsen_scan_bnd(BndParams p)
     State st[VEC];
 #pragma unroll
     for (int v = 0; v < VEC; ++v) {
-        st[v].lx = lds_startL[lane * VEC + v];
-        st[v].s = lds_startS[lane * VEC + v];
+        st[v].lx = lds_startL[loff + v];
+        st[v].s = lds_startS[loff + v];
         if (w > 0) st[v] = seg_apply<SIGNED>(st[v], pre[v]);
     }
     float *op = p.out + ubase;
@@ -362,10 +314,7 @@ __global__ __launch_bounds__(NW * 64, MINW) void heinsen_scan_bnd(BndParams p)
         if (full || (chan_ok && t0 + k < p.n)) store_vec(op + (int64_t)k * p.D + loff, o);
         if (SB) __builtin_amdgcn_sched_barrier(0);
     }
-
     HS_STAMP(7);
-    // Take this tile off the reader counts of the records it used (nothing waits for these).
-    if (need_agg || need_st) (void)__hip_atomic_fetch_sub(fp, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
 // ---- host side ------------------------------------------------------------------------------------
@@ -378,14 +327,13 @@ struct BndPlan {
     int vec, T, NW, G, CH, variant;
     int cols_per_b, ncols, nchunks, ngroups;
     uint32_t ntiles;
-    size_t off_agg_flag, off_st_flag, flag_bytes;                      // inside the flag buffer
-    size_t off_agg_A, off_agg_M, off_agg_S, off_st_L, off_st_S, data_bytes; // inside the data buffer
+    size_t off_agg, off_state, records; // in records, relative to kRecordBase
 };
 
 #ifdef HS_TUNING
 // tuning variants (signed float32 only, development builds): ID, VEC, T, NW, G, MINW, SB
 #define HS_VARIANTS(X) \
-    X(1, 2, 16, 8, 8, 2, false) X(2, 2, 16, 8, 4, 2, false) X(3, 1, 16, 16, 2, 8, true) X(4, 1, 16, 16, 8, 8, true) \
+    X(1, 2, 16, 8, 8, 2, false) X(2, 2, 16, 8, 4, 4, true) X(3, 1, 16, 16, 2, 8, true) X(4, 1, 16, 16, 8, 8, true) \
     X(5, 1, 32, 16, 4, 4, true) X(6, 1, 32, 8, 4, 4, true) X(7, 1, 32, 8, 2, 4, true) X(8, 1, 32, 8, 8, 4, true) \
     X(9, 1, 16, 16, 4, 8, false) X(10, 1, 24, 8, 4, 6, true) X(11, 1, 24, 16, 4, 6, true) X(12, 1, 8, 16, 4, 8, true) \
     X(13, 1, 32, 8, 4, 5, true) X(14, 1, 16, 16, 4, 8, true) X(15, 1, 16, 8, 4, 8, true) X(16, 1, 20, 16, 4, 6, true)
@@ -433,26 +381,14 @@ BndPlan make_plan(const ScanCall &c)
     pl.nchunks = (int)ceil_div(c.n, (int64_t)pl.NW * pl.T);
     pl.ngroups = (int)ceil_div(pl.nchunks, pl.G);
     pl.ntiles = (uint32_t)pl.ncols * (uint32_t)pl.nchunks;
-    size_t off = 64; // counters
-    pl.off_agg_flag = off;
-    off += (size_t)pl.ntiles * 4;
-    pl.off_st_flag = off;
-    off += (size_t)pl.ngroups * pl.ncols * 4;
-    pl.flag_bytes = align_up(off, 256);
-    off = 0;
-    const size_t agg = (size_t)pl.ntiles * pl.CH * 4;
-    const size_t stt = (size_t)pl.ngroups * pl.ncols * pl.CH * 4;
-    pl.off_agg_A = off; off += align_up(agg, 256);
-    pl.off_agg_M = off; off += align_up(agg, 256);
-    pl.off_agg_S = off; off += align_up(agg, 256);
-    pl.off_st_L = off; off += align_up(stt, 256);
-    pl.off_st_S = off; off += align_up(stt, 256);
-    pl.data_bytes = off;
+    pl.off_agg = 0;
+    pl.off_state = (size_t)pl.ntiles * 2 * pl.CH;
+    pl.records = pl.off_state + (size_t)pl.ngroups * pl.ncols * pl.CH;
     return pl;
 }
 
 template <bool SIGNED, bool LOG_IN, bool LOG_OUT, typename InT>
-hipError_t launch_mode(const ScanCall &c, const BndPlan &pl, char *flags, char *data)
+hipError_t launch_mode(const ScanCall &c, const BndPlan &pl, rec_t *records, LaunchTag tag)
 {
     BndParams p;
     p.a = c.a;
@@ -465,15 +401,11 @@ hipError_t launch_mode(const ScanCall &c, const BndPlan &pl, char *flags, char *
     p.cols_per_b = pl.cols_per_b;
     p.ncols = pl.ncols;
     p.nchunks = pl.nchunks;
-    p.ntiles = pl.ntiles;
-    p.counters = reinterpret_cast<uint32_t *>(flags);
-    p.agg_flag = reinterpret_cast<uint32_t *>(flags + pl.off_agg_flag);
-    p.st_flag = reinterpret_cast<uint32_t *>(flags + pl.off_st_flag);
-    p.agg_A = reinterpret_cast<float *>(data + pl.off_agg_A);
-    p.agg_M = reinterpret_cast<float *>(data + pl.off_agg_M);
-    p.agg_S = reinterpret_cast<uint32_t *>(data + pl.off_agg_S);
-    p.st_L = reinterpret_cast<float *>(data + pl.off_st_L);
-    p.st_S = reinterpret_cast<uint32_t *>(data + pl.off_st_S);
+    p.epoch = tag.epoch;
+    p.ticket_base = tag.ticket_base;
+    p.ticket = records;
+    p.agg = records + kRecordBase + pl.off_agg;
+    p.state = records + kRecordBase + pl.off_state;
 #ifdef HS_TRACE
     if (!g_trace) (void)hipMalloc(&g_trace, (size_t)(1u << 20) * 8 * sizeof(unsigned long long));
     p.trace = g_trace;
@@ -498,9 +430,9 @@ hipError_t launch_mode(const ScanCall &c, const BndPlan &pl, char *flags, char *
     return hipGetLastError();
 }
 
-hipError_t launch_dispatch(const ScanCall &c, const BndPlan &pl, char *flags, char *data)
+hipError_t launch_dispatch(const ScanCall &c, const BndPlan &pl, rec_t *records, LaunchTag tag)
 {
-    HS_DISPATCH_MODE(c, launch_mode, c, pl, flags, data);
+    HS_DISPATCH_MODE(c, launch_mode, c, pl, records, tag);
 }
 
 } // namespace
@@ -508,13 +440,13 @@ hipError_t launch_dispatch(const ScanCall &c, const BndPlan &pl, char *flags, ch
 ScratchNeed bnd_scratch(const ScanCall &c)
 {
     BndPlan pl = make_plan(c);
-    return ScratchNeed{pl.flag_bytes, pl.data_bytes};
+    return ScratchNeed{pl.records, pl.ntiles};
 }
 
-hipError_t bnd_launch(const ScanCall &c, void *flags, void *data)
+hipError_t bnd_launch(const ScanCall &c, unsigned long long *records, LaunchTag tag)
 {
     BndPlan pl = make_plan(c);
-    return launch_dispatch(c, pl, static_cast<char *>(flags), static_cast<char *>(data));
+    return launch_dispatch(c, pl, records, tag);
 }
 
 const char *bnd_kernel_name(const ScanCall &) { return "heinsen_scan_bnd"; }
