@@ -16,6 +16,9 @@
 #include "heinsen_math.hpp"
 
 namespace hs {
+#ifdef HS_TRACE
+extern unsigned long long *g_trace_bdn_storage;
+#endif
 namespace {
 
 // ---- lane-level pieces shared by both kernels --------------------------------------------------------
@@ -288,7 +291,22 @@ struct TileParams {
     rec_t *ticket;
     rec_t *recs;           // per row: level-1, level-2, level-3 summaries (2 records each), states (2 records each)
     uint32_t off2, off3, off4, row_stride; // record offsets of levels 2, 3 and the states inside a row's block
+#ifdef HS_TRACE
+    unsigned long long *trace;
+#endif
 };
+
+#ifdef HS_TRACE
+#define HS_STAMP(i)                                                              \
+    do {                                                                         \
+        if (threadIdx.x == 0) p.trace[(size_t)tile * 8 + (i)] = wall_clock64(); \
+    } while (0)
+#define g_trace_bdn ::hs::g_trace_bdn_storage
+#else
+#define HS_STAMP(i) \
+    do {            \
+    } while (0)
+#endif
 
 struct State64 {
     double lx;
@@ -340,6 +358,7 @@ __global__ __launch_bounds__(kTileWaves * 64) void heinsen_scan_tiles(TileParams
         __syncthreads();
         tile = __builtin_amdgcn_readfirstlane(s_tile);
     }
+    HS_STAMP(0);
     const int64_t row = tile / p.tpr;
     const uint32_t c = tile % p.tpr;
     const InT *arow = reinterpret_cast<const InT *>(p.a) + row * p.n;
@@ -360,24 +379,43 @@ __global__ __launch_bounds__(kTileWaves * 64) void heinsen_scan_tiles(TileParams
         if (lvl == 2 && (uint32_t)sub < r) { need = true; fp = rrow + 2 * (size_t)(((c >> 4) << 4) + sub); }
         if (lane == 63 && sb > 0) { need = true; fp = rrow + p.off4 + 2 * (size_t)sb; }
     }
-    auto fetch_records = [&]() -> bool {
-        bool ok = true;
-        if (need) {
+    bool got = !need; // this lane's records are in
+    auto fetch_records = [&]() -> uint64_t {
+        if (!got) {
             ra = rec_get(fp);
             rm = rec_get(fp + 1);
-            ok = rec_ok(ra, p.epoch) && rec_ok(rm, p.epoch);
+            got = rec_ok(ra, p.epoch) && rec_ok(rm, p.epoch);
         }
-        return __builtin_amdgcn_ballot_w64(!ok) == 0ull;
+        return __builtin_amdgcn_ballot_w64(got);
     };
-    bool have_records = false;
-    if (MULTI && w == 0) have_records = fetch_records();
+    uint64_t have = 0;
+    if (MULTI && w == 0) have = fetch_records();
 
+    // global <-> lane traffic of each wave goes through its own LDS region (coalesced both ways)
+    __shared__ u32x4 stage[VECIO ? NW : 1][VECIO ? 64 * (ITEMS / 4 + 1) : 1];
+    const int64_t wstart = (int64_t)c * kTile + (int64_t)w * (64 * ITEMS); // first element of this wave
     float Av[ITEMS], Mv[ITEMS];
     uint32_t sw;
-    lane_load<LOG_IN, InT, ITEMS, VECIO>(arow, brow, start, p.n, Av, Mv);
+    if (VECIO) {
+        constexpr int VL = 16 / (int)sizeof(InT);
+        constexpr int NVI = ITEMS / VL;
+        const uint32_t one = sizeof(InT) == 4 ? 0x3f800000u : 0x3f803f80u;
+        const uint32_t ninf = sizeof(InT) == 4 ? 0xff800000u : 0xff80ff80u;
+        const uint32_t fa = LOG_IN ? 0u : one, fb = LOG_IN ? ninf : 0u;
+        int64_t n_vec = (p.n - wstart) / VL; // vectors of the row left from this wave's first element
+        n_vec = n_vec < 0 ? 0 : n_vec;
+        u32x4 va[NVI], vb[NVI];
+        wave_load_blocked<NVI>(reinterpret_cast<const u32x4 *>(arow + wstart), n_vec, u32x4{fa, fa, fa, fa}, stage[w], lane, va);
+        wave_load_blocked<NVI>(reinterpret_cast<const u32x4 *>(brow + wstart), n_vec, u32x4{fb, fb, fb, fb}, stage[w], lane, vb);
+        unpack_inputs<InT, NVI, ITEMS>(va, Av);
+        unpack_inputs<InT, NVI, ITEMS>(vb, Mv);
+    } else {
+        lane_load<LOG_IN, InT, ITEMS, false>(arow, brow, start, p.n, Av, Mv);
+    }
     Seg mine = lane_scan<SIGNED, LOG_IN, LOG_OUT, ITEMS>(Av, Mv, sw);
     Seg incl = wave_inclusive_scan<SIGNED>(mine);
     Seg lane_excl = wave_shift_up<SIGNED>(incl);
+    HS_STAMP(1);
     if (lane == 63) {
         lds_A[w] = incl.A;
         lds_M[w] = incl.M;
@@ -406,17 +444,42 @@ __global__ __launch_bounds__(kTileWaves * 64) void heinsen_scan_tiles(TileParams
             encode<SIGNED, LOG_IN>(p.x0[p.x0_stride ? row : 0], lx, st.s);
             st.lx = (double)lx;
         }
+        HS_STAMP(2);
         if (MULTI) {
             if (more && r < 15u && lane == 0) seg_put<SIGNED>(rrow + 2 * (size_t)c, rrow + 2 * (size_t)c + 1, total, p.epoch);
-            if (!have_records) {
-                while (!fetch_records()) __builtin_amdgcn_s_sleep(2);
+            // Levels arrive independently and what this tile owes to later tiles is published as soon as
+            // its inputs are in: the group summary needs level 1 only, the block summary levels 1 and 2,
+            // so no tile ever waits for a chain of other tiles' waits.
+            const bool lead2 = more && r == 15u;            // folds its group of 16 tiles
+            const bool lead3 = lead2 && g == 15u;           // ... and its block of 16 groups
+            bool pub2 = !lead2, pub3 = !lead3;
+            Seg f1 = seg_identity(), f2 = seg_identity(), f3 = seg_identity(), a2 = seg_identity();
+            const uint64_t m1 = 0x0000ffff00000000ull, m2 = 0x00000000ffff0000ull, all = ~0ull;
+            for (;;) {
+                if ((!pub2 && (have & m1) == m1) || (!pub3 && (have & (m1 | m2)) == (m1 | m2)) || have == all) {
+                    Seg part = (need && got && lane < 48) ? seg_from<SIGNED>(ra, rm) : seg_identity();
+                    part = row16_inclusive_scan<SIGNED>(part);
+                    f3 = seg_readlane<SIGNED>(part, 15);
+                    f2 = seg_readlane<SIGNED>(part, 31);
+                    f1 = seg_readlane<SIGNED>(part, 47);
+                    if (!pub2) {
+                        a2 = seg_combine<SIGNED>(f1, total); // this group of 16 tiles
+                        if (g < 15u && lane == 0)
+                            seg_put<SIGNED>(rrow + p.off2 + 2 * (size_t)(c >> 4), rrow + p.off2 + 2 * (size_t)(c >> 4) + 1, a2, p.epoch);
+                        pub2 = true;
+                    }
+                    if (!pub3 && (have & (m1 | m2)) == (m1 | m2)) {
+                        const Seg a3 = seg_combine<SIGNED>(f2, a2); // this block of 256 tiles
+                        if (q < 15u && lane == 0)
+                            seg_put<SIGNED>(rrow + p.off3 + 2 * (size_t)(c >> 8), rrow + p.off3 + 2 * (size_t)(c >> 8) + 1, a3, p.epoch);
+                        pub3 = true;
+                    }
+                }
+                if (have == all) break;
+                __builtin_amdgcn_s_sleep(2);
+                have = fetch_records();
             }
-            // folds of the three levels, each in index order inside its row of 16 lanes
-            Seg part = (need && lane < 48) ? seg_from<SIGNED>(ra, rm) : seg_identity();
-            part = row16_inclusive_scan<SIGNED>(part);
-            const Seg f3 = seg_readlane<SIGNED>(part, 15);
-            const Seg f2 = seg_readlane<SIGNED>(part, 31);
-            const Seg f1 = seg_readlane<SIGNED>(part, 47);
+            HS_STAMP(3);
             if (sb > 0) {
                 // lane 63 holds the super-block state: payloads are the high and low word of the double,
                 // the sign rides in the user bits of the first record
@@ -427,26 +490,18 @@ __global__ __launch_bounds__(kTileWaves * 64) void heinsen_scan_tiles(TileParams
                 st.s = SIGNED ? (sg << 31) : 0u;
             }
             const State64 st3 = seg_apply64<SIGNED>(st, f3); // state at the start of the 256-tile block
-            if (more && r == 15u) {
-                const Seg a2 = seg_combine<SIGNED>(f1, total); // this group of 16 tiles
-                if (g < 15u) {
-                    if (lane == 0) seg_put<SIGNED>(rrow + p.off2 + 2 * (size_t)(c >> 4), rrow + p.off2 + 2 * (size_t)(c >> 4) + 1, a2, p.epoch);
-                } else {
-                    const Seg a3 = seg_combine<SIGNED>(f2, a2); // this block of 256 tiles
-                    if (q < 15u) {
-                        if (lane == 0) seg_put<SIGNED>(rrow + p.off3 + 2 * (size_t)(c >> 8), rrow + p.off3 + 2 * (size_t)(c >> 8) + 1, a3, p.epoch);
-                    } else {
-                        const State64 nx = seg_apply64<SIGNED>(st3, a3); // start of the next super-block
-                        const unsigned long long bits = (unsigned long long)__double_as_longlong(nx.lx);
-                        if (lane == 0) {
-                            rec_put(rrow + p.off4 + 2 * (size_t)(sb + 1), (uint32_t)(bits >> 32), p.epoch, SIGNED ? (nx.s >> 31) : 0u);
-                            rec_put(rrow + p.off4 + 2 * (size_t)(sb + 1) + 1, (uint32_t)bits, p.epoch, 0u);
-                        }
-                    }
+            if (lead3 && q == 15u) {
+                const Seg a3 = seg_combine<SIGNED>(f2, a2);
+                const State64 nx = seg_apply64<SIGNED>(st3, a3); // start of the next super-block
+                const unsigned long long bits = (unsigned long long)__double_as_longlong(nx.lx);
+                if (lane == 0) {
+                    rec_put(rrow + p.off4 + 2 * (size_t)(sb + 1), (uint32_t)(bits >> 32), p.epoch, SIGNED ? (nx.s >> 31) : 0u);
+                    rec_put(rrow + p.off4 + 2 * (size_t)(sb + 1) + 1, (uint32_t)bits, p.epoch, 0u);
                 }
             }
             st = seg_apply64<SIGNED>(seg_apply64<SIGNED>(st3, f2), f1);
         }
+        HS_STAMP(4);
         if (lane == 0) {
             lds_startL = (float)st.lx;
             lds_startS = st.s;
@@ -454,11 +509,28 @@ __global__ __launch_bounds__(kTileWaves * 64) void heinsen_scan_tiles(TileParams
     }
     __syncthreads();
 
+    HS_STAMP(5);
     State st;
     st.lx = lds_startL;
     st.s = lds_startS;
     st = seg_apply<SIGNED>(st, seg_combine<SIGNED>(wave_excl, lane_excl));
-    lane_emit<SIGNED, LOG_OUT, ITEMS, VECIO>(p.out + row * p.n, start, p.n, st, Av, Mv, sw);
+    if (VECIO) {
+        constexpr int NVO = ITEMS / 4;
+        const uint32_t swx = fold_state_sign<SIGNED>(sw, st);
+        u32x4 vo[NVO];
+#pragma unroll
+        for (int qv = 0; qv < NVO; ++qv)
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+                vo[qv][i] = f2u(emit<SIGNED, LOG_OUT>(st, Av[qv * 4 + i], Mv[qv * 4 + i], swx, qv * 4 + i));
+        int64_t n_vec = (p.n - wstart) / 4;
+        n_vec = n_vec < 0 ? 0 : n_vec;
+        wave_store_blocked<NVO>(reinterpret_cast<u32x4 *>(p.out + row * p.n + wstart), n_vec, stage[w], lane, vo);
+    } else {
+        lane_emit<SIGNED, LOG_OUT, ITEMS, false>(p.out + row * p.n, start, p.n, st, Av, Mv, sw);
+    }
+    HS_STAMP(6);
+    HS_STAMP(7);
 }
 
 // ---- host side -------------------------------------------------------------------------------------------
@@ -546,6 +618,10 @@ hipError_t launch_mode(const ScanCall &c, const BdnPlan &pl, rec_t *records, Lau
     p.off3 = pl.off3;
     p.off4 = pl.off4;
     p.row_stride = pl.row_stride;
+#ifdef HS_TRACE
+    if (!g_trace_bdn) (void)hipMalloc(&g_trace_bdn, (size_t)(1u << 20) * 8 * sizeof(unsigned long long));
+    p.trace = g_trace_bdn;
+#endif
     dim3 grid(pl.ntiles), block(kTileWaves * 64);
 #define HS_TILES(VEC_, MULTI_) \
     hipLaunchKernelGGL((heinsen_scan_tiles<SIGNED, LOG_IN, LOG_OUT, InT, VEC_, MULTI_>), grid, block, 0, c.stream, p)
@@ -578,6 +654,15 @@ hipError_t bdn_launch(const ScanCall &c, unsigned long long *records, LaunchTag 
     BdnPlan pl = make_plan(c);
     return launch_dispatch(c, pl, records, tag);
 }
+
+#ifdef HS_TRACE
+namespace { }
+unsigned long long *g_trace_bdn_storage = nullptr;
+extern "C" int heinsen_debug_trace_bdn(unsigned long long *host, size_t ntiles)
+{
+    return (int)hipMemcpy(host, g_trace_bdn_storage, ntiles * 8 * sizeof(unsigned long long), hipMemcpyDeviceToHost);
+}
+#endif
 
 const char *bdn_kernel_name(const ScanCall &c)
 {
