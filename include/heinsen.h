@@ -49,7 +49,8 @@ typedef enum {
     HEINSEN_OK = 0,
     HEINSEN_ERR_INVALID_ARG = 1, /* null pointer, non-positive size, size overflow, misaligned pointer,
                                     unknown layout or flag bit                                           */
-    HEINSEN_ERR_UNSUPPORTED = 2, /* a legal but unimplemented combination (LOG_OUTPUT on a signed domain) */
+    HEINSEN_ERR_UNSUPPORTED = 2, /* a legal but unimplemented combination: LOG_OUTPUT on a signed domain,
+                                    a call that needs scratch while its stream is being captured       */
     HEINSEN_ERR_ALLOC = 3,       /* scratch memory could not be allocated; nothing was launched          */
     HEINSEN_ERR_HIP = 4          /* a HIP runtime call failed; see heinsen_last_hip_error()              */
 } heinsen_status_t;
@@ -74,9 +75,13 @@ typedef enum {
  * returned status covers argument validation, scratch allocation and launch errors only.
  *
  * Scratch: a grow-only buffer per (device, stream) holds the inter-tile carries.  It is allocated
- * with hipMalloc on the first call that needs it or needs more (that call may synchronise the
- * device); later calls of the same or smaller shape allocate nothing.  Calls on different streams
- * never share scratch.  Kernels leave the scratch clean on completion, so a launch may be replayed.
+ * with hipMalloc on the first call that needs it or needs more (that call synchronises the stream
+ * if it replaces a buffer); later calls of the same or smaller shape allocate nothing.  Calls on
+ * different streams never share scratch; calls on one stream may come from several host threads.
+ * Carries of different launches are told apart by a launch counter kept on the host, so a call that
+ * is being recorded into a HIP graph (stream capture) is refused with HEINSEN_ERR_UNSUPPORTED: a
+ * replay would meet its own stale carries.  Shapes that need no carries (rows of at most 2048
+ * steps in the [B, D, n] layout, or any single-tile row) use no scratch and may be captured.
  *
  * Data-dependent conditions are not errors and follow IEEE arithmetic: a NaN input gives NaN from
  * that step on in that sequence only; a_t = 0 restarts the sequence at b_t; b_t = 0 and x_0 = 0 are
