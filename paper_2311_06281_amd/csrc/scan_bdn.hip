@@ -149,14 +149,14 @@ __device__ __forceinline__ void wave_load_blocked(const u32x4 *row, int64_t n_ve
                                                   u32x4 (&v)[NV])
 {
     if (NV == 1) {
-        v[0] = (lane < n_vec) ? row[lane] : fill;
+        v[0] = (lane < n_vec) ? __builtin_nontemporal_load(row + lane) : fill;
         return;
     }
     u32x4 t[NV];
 #pragma unroll
     for (int j = 0; j < NV; ++j) {
         const int c = j * 64 + lane;
-        t[j] = (c < n_vec) ? row[c] : fill;
+        t[j] = (c < n_vec) ? __builtin_nontemporal_load(row + c) : fill; // streamed once: keep it out of the caches' way
     }
 #pragma unroll
     for (int j = 0; j < NV; ++j) {
@@ -185,7 +185,7 @@ __device__ __forceinline__ void wave_store_blocked(u32x4 *row, int64_t n_vec, u3
 #pragma unroll
     for (int j = 0; j < NV; ++j) {
         const int c = j * 64 + lane;
-        if (c < n_vec) row[c] = t[j];
+        if (c < n_vec) __builtin_nontemporal_store(t[j], row + c);
     }
     wave_lds_order();
 }

@@ -36,6 +36,11 @@ struct BndParams {
 #ifdef HS_TRACE
     unsigned long long *trace; // [ntiles][8] wall-clock stamps of wave 0 (100 MHz), development only
 #endif
+#ifdef HS_TUNING
+    uint32_t stagger_lo, stagger_hi;
+    int stagger_ticks;
+    int ablate; // bit0: no waiting for carries, bit1: no arithmetic, bit2: tile = blockIdx (no ticket)
+#endif
 };
 
 #ifdef HS_TRACE
@@ -52,15 +57,16 @@ struct BndParams {
 template <typename InT, int VEC>
 __device__ __forceinline__ void load_vec(const InT *p, float (&v)[VEC])
 {
+    // every element is touched once: non-temporal accesses keep the stream out of the caches' way
     typedef InT vec_t __attribute__((ext_vector_type(VEC)));
-    vec_t x = *reinterpret_cast<const vec_t *>(p);
+    vec_t x = __builtin_nontemporal_load(reinterpret_cast<const vec_t *>(p));
 #pragma unroll
     for (int i = 0; i < VEC; ++i) v[i] = widen(x[i]);
 }
 template <typename InT>
 __device__ __forceinline__ void load_vec(const InT *p, float (&v)[1])
 {
-    v[0] = widen(*p);
+    v[0] = widen(__builtin_nontemporal_load(p));
 }
 
 template <int VEC>
@@ -70,9 +76,9 @@ __device__ __forceinline__ void store_vec(float *p, const float (&v)[VEC])
     vec_t x;
 #pragma unroll
     for (int i = 0; i < VEC; ++i) x[i] = v[i];
-    *reinterpret_cast<vec_t *>(p) = x;
+    __builtin_nontemporal_store(x, reinterpret_cast<vec_t *>(p));
 }
-__device__ __forceinline__ void store_vec(float *p, const float (&v)[1]) { *p = v[0]; }
+__device__ __forceinline__ void store_vec(float *p, const float (&v)[1]) { __builtin_nontemporal_store(v[0], p); }
 
 __device__ __forceinline__ uint32_t pack_signs(const Seg &g) { return (g.sA >> 31) | ((g.sM >> 31) << 1); }
 __device__ __forceinline__ void unpack_signs(uint32_t s, Seg &g)
@@ -102,11 +108,22 @@ __global__ __launch_bounds__(NW * 64, MINW) void heinsen_scan_bnd(BndParams p)
 
     // Tiles are handed out in start order, so every tile a workgroup may wait for (same column,
     // earlier chunk => smaller ticket) belongs to a workgroup that is already running.
+#ifdef HS_TUNING
+    if (p.ablate & 4) {
+        if (threadIdx.x == 0) s_tile = blockIdx.x;
+    } else
+#endif
     if (threadIdx.x == 0)
         s_tile = __hip_atomic_fetch_add(reinterpret_cast<uint32_t *>(p.ticket), 1u, __ATOMIC_RELAXED,
                                         __HIP_MEMORY_SCOPE_AGENT) - p.ticket_base;
     __syncthreads();
     const uint32_t tile = __builtin_amdgcn_readfirstlane(s_tile);
+#ifdef HS_TUNING
+    if (p.stagger_ticks > 0 && tile >= p.stagger_lo && tile < p.stagger_hi) {
+        const unsigned long long t_start = wall_clock64();
+        while (wall_clock64() - t_start < (unsigned long long)p.stagger_ticks) __builtin_amdgcn_s_sleep(32);
+    }
+#endif
     HS_STAMP(0);
     const int chunk = (int)(tile / (uint32_t)p.ncols);
     const int col = (int)(tile % (uint32_t)p.ncols);
@@ -128,15 +145,11 @@ __global__ __launch_bounds__(NW * 64, MINW) void heinsen_scan_bnd(BndParams p)
     //      kernel is past its first round the earlier tiles of the group have usually published, and the
     //      records then arrive ahead of the tile's own loads at no cost in latency --------------------
     rec_t rA[GP][VEC], rM[GP][VEC], rS[VEC];
-    auto fetch_records = [&]() -> bool {
-        bool ok = true;
+    auto issue_records = [&]() {
         if (g > 0) {
             const rec_t *sp = p.state + ((size_t)g * p.ncols + col) * CH + loff;
 #pragma unroll
-            for (int v = 0; v < VEC; ++v) {
-                rS[v] = rec_get(sp + v);
-                ok = ok && rec_ok(rS[v], p.epoch);
-            }
+            for (int v = 0; v < VEC; ++v) rS[v] = rec_get(sp + v);
         }
 #pragma unroll
         for (int j = 0; j < G - 1; ++j) {
@@ -146,14 +159,27 @@ __global__ __launch_bounds__(NW * 64, MINW) void heinsen_scan_bnd(BndParams p)
                 for (int v = 0; v < VEC; ++v) {
                     rA[j][v] = rec_get(tp + v);
                     rM[j][v] = rec_get(tp + CH + v);
-                    ok = ok && rec_ok(rA[j][v], p.epoch) && rec_ok(rM[j][v], p.epoch);
                 }
+            }
+        }
+    };
+    auto records_in = [&]() -> bool {
+        bool ok = true;
+        if (g > 0) {
+#pragma unroll
+            for (int v = 0; v < VEC; ++v) ok = ok && rec_ok(rS[v], p.epoch);
+        }
+#pragma unroll
+        for (int j = 0; j < G - 1; ++j) {
+            if (j < r) {
+#pragma unroll
+                for (int v = 0; v < VEC; ++v) ok = ok && rec_ok(rA[j][v], p.epoch) && rec_ok(rM[j][v], p.epoch);
             }
         }
         return __builtin_amdgcn_ballot_w64(!ok) == 0ull;
     };
     bool have_records = false;
-    if (w == 0) have_records = fetch_records();
+    if (w == 0) issue_records();
 
     // ---- load: the lane's T x VEC inputs -------------------------------------------------------
     float Av[T][VEC], Mv[T][VEC];
@@ -181,11 +207,19 @@ __global__ __launch_bounds__(NW * 64, MINW) void heinsen_scan_bnd(BndParams p)
         }
     }
 
+#ifdef HS_TUNING
+    if (p.ablate & 1) have_records = true; else
+#endif
+    if (w == 0) have_records = records_in(); // first look: answered while the tile's loads were in flight
+
     // ---- encode + serial scan in each lane; Av/Mv become the per-element records (see stash) --------
     uint32_t sw[VEC];
     Seg run[VEC];
 #pragma unroll
     for (int v = 0; v < VEC; ++v) sw[v] = 0u;
+#ifdef HS_TUNING
+    if (!(p.ablate & 2))
+#endif
 #pragma unroll
     for (int k = 0; k < T; ++k) {
 #pragma unroll
@@ -208,6 +242,9 @@ __global__ __launch_bounds__(NW * 64, MINW) void heinsen_scan_bnd(BndParams p)
     }
 
     HS_STAMP(1);
+    // second look, asked now and read after the barrier and the fold below
+    if (w == 0 && !have_records) issue_records();
+
     // ---- chain the waves of the workgroup through LDS ------------------------------------------
 #pragma unroll
     for (int v = 0; v < VEC; ++v) {
@@ -251,7 +288,10 @@ __global__ __launch_bounds__(NW * 64, MINW) void heinsen_scan_bnd(BndParams p)
         }
         HS_STAMP(3);
         if (!have_records) {
-            while (!fetch_records()) __builtin_amdgcn_s_sleep(2);
+            while (!records_in()) {
+                __builtin_amdgcn_s_sleep(2);
+                issue_records();
+            }
         }
         HS_STAMP(4);
         State st[VEC];
@@ -311,6 +351,12 @@ __global__ __launch_bounds__(NW * 64, MINW) void heinsen_scan_bnd(BndParams p)
         float o[VEC];
 #pragma unroll
         for (int v = 0; v < VEC; ++v) o[v] = emit<SIGNED, LOG_OUT>(st[v], Av[k][v], Mv[k][v], swx[v], k);
+#ifdef HS_TUNING
+        if (p.ablate & 2) {
+#pragma unroll
+            for (int v = 0; v < VEC; ++v) o[v] = Av[k][v] + Mv[k][v];
+        }
+#endif
         if (full || (chan_ok && t0 + k < p.n)) store_vec(op + (int64_t)k * p.D + loff, o);
         if (SB) __builtin_amdgcn_sched_barrier(0);
     }
@@ -333,10 +379,10 @@ struct BndPlan {
 #ifdef HS_TUNING
 // tuning variants (signed float32 only, development builds): ID, VEC, T, NW, G, MINW, SB
 #define HS_VARIANTS(X) \
-    X(1, 2, 16, 8, 8, 2, false) X(2, 2, 16, 8, 4, 4, true) X(3, 1, 16, 16, 2, 8, true) X(4, 1, 16, 16, 8, 8, true) \
-    X(5, 1, 32, 16, 4, 4, true) X(6, 1, 32, 8, 4, 4, true) X(7, 1, 32, 8, 2, 4, true) X(8, 1, 32, 8, 8, 4, true) \
-    X(9, 1, 16, 16, 4, 8, false) X(10, 1, 24, 8, 4, 6, true) X(11, 1, 24, 16, 4, 6, true) X(12, 1, 8, 16, 4, 8, true) \
-    X(13, 1, 32, 8, 4, 5, true) X(14, 1, 16, 16, 4, 8, true) X(15, 1, 16, 8, 4, 8, true) X(16, 1, 20, 16, 4, 6, true)
+    X(1, 4, 4, 16, 4, 4, true) X(2, 4, 8, 8, 4, 4, true) X(3, 4, 16, 4, 4, 2, true) X(4, 2, 8, 16, 4, 4, true) \
+    X(5, 2, 16, 8, 4, 4, true) X(6, 2, 32, 4, 4, 2, true) X(7, 1, 16, 16, 4, 8, true) X(8, 1, 32, 8, 4, 4, true) \
+    X(9, 4, 8, 16, 4, 2, true) X(10, 2, 16, 16, 4, 2, true) X(11, 4, 4, 8, 4, 4, true) X(12, 4, 2, 16, 4, 8, true) \
+    X(13, 1, 8, 16, 4, 8, true) X(14, 2, 4, 16, 4, 8, true) X(15, 1, 16, 8, 4, 8, true) X(16, 2, 8, 8, 4, 8, true)
 constexpr int kVariants[][4] = {{0, 0, 0, 0},
 #define X(ID, V, T_, NW_, G_, MW, SB_) {V, T_, NW_, G_},
                                 HS_VARIANTS(X)
@@ -350,15 +396,16 @@ BndPlan make_plan(const ScanCall &c)
     BndPlan pl;
     const size_t in_sz = c.bf16 ? 2 : 4;
     auto aligned = [](const void *ptr, size_t a) { return (reinterpret_cast<uintptr_t>(ptr) % a) == 0; };
-    // float32: one channel per lane, 16 steps per wave, 16 waves (tile = 64 channels x 256 steps, 62
-    // VGPRs, two workgroups per CU) measured best on MI355X; bf16 takes two channels per lane so that a
-    // wave still reads 256 contiguous bytes per step.
+    // float32: one channel per lane, 32 steps per wave, 8 waves (tile = 64 channels x 256 steps, <= 128
+    // VGPRs, two workgroups per CU) measured best on MI355X among the shapes tried; bf16 takes two
+    // channels per lane so that a wave still reads 256 contiguous bytes per step.
     pl.vec = 1;
-    pl.T = 16;
-    pl.NW = 16;
+    pl.T = 32;
+    pl.NW = 8;
     pl.G = 4;
     if (c.bf16 && c.D % 2 == 0 && aligned(c.a, 2 * in_sz) && aligned(c.b, 2 * in_sz) && aligned(c.out, 8)) {
         pl.vec = 2;
+        pl.T = 16;
         pl.NW = 8;
     }
     pl.variant = 0;
@@ -406,6 +453,12 @@ hipError_t launch_mode(const ScanCall &c, const BndPlan &pl, rec_t *records, Lau
     p.ticket = records;
     p.agg = records + kRecordBase + pl.off_agg;
     p.state = records + kRecordBase + pl.off_state;
+#ifdef HS_TUNING
+    p.ablate = getenv("HEINSEN_ABLATE") ? atoi(getenv("HEINSEN_ABLATE")) : 0;
+    p.stagger_ticks = getenv("HEINSEN_STAGGER") ? atoi(getenv("HEINSEN_STAGGER")) : 0;
+    p.stagger_lo = getenv("HEINSEN_STAGGER_LO") ? atoi(getenv("HEINSEN_STAGGER_LO")) : 256;
+    p.stagger_hi = getenv("HEINSEN_STAGGER_HI") ? atoi(getenv("HEINSEN_STAGGER_HI")) : 512;
+#endif
 #ifdef HS_TRACE
     if (!g_trace) (void)hipMalloc(&g_trace, (size_t)(1u << 20) * 8 * sizeof(unsigned long long));
     p.trace = g_trace;
@@ -426,7 +479,7 @@ hipError_t launch_mode(const ScanCall &c, const BndPlan &pl, rec_t *records, Lau
     if (pl.vec == 2)
         hipLaunchKernelGGL((heinsen_scan_bnd<SIGNED, LOG_IN, LOG_OUT, InT, 2, 16, 8, 4, 4, true>), grid, block, 0, c.stream, p);
     else
-        hipLaunchKernelGGL((heinsen_scan_bnd<SIGNED, LOG_IN, LOG_OUT, InT, 1, 16, 16, 4, 8, true>), grid, block, 0, c.stream, p);
+        hipLaunchKernelGGL((heinsen_scan_bnd<SIGNED, LOG_IN, LOG_OUT, InT, 1, 32, 8, 4, 4, true>), grid, block, 0, c.stream, p);
     return hipGetLastError();
 }
 
