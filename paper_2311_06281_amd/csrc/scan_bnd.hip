@@ -25,6 +25,7 @@ struct BndParams {
     float *out;
     int64_t D, n;
     int x0_stride;    // 0: one x0 for all, 1: x0[b*D + d]
+    int stream_out;   // 1: the output does not fit the last-level cache, write it non-temporally
     int cols_per_b;   // ceil(D / CH)
     int ncols;        // B * cols_per_b
     int nchunks;      // ceil(n / (NW*T))
@@ -69,16 +70,27 @@ __device__ __forceinline__ void load_vec(const InT *p, float (&v)[1])
     v[0] = widen(__builtin_nontemporal_load(p));
 }
 
+// stream: the output is larger than the last-level cache and is written past it; otherwise it is
+// written normally and stays cached for whoever consumes it next.
 template <int VEC>
-__device__ __forceinline__ void store_vec(float *p, const float (&v)[VEC])
+__device__ __forceinline__ void store_vec(float *p, const float (&v)[VEC], bool stream)
 {
     typedef float vec_t __attribute__((ext_vector_type(VEC)));
     vec_t x;
 #pragma unroll
     for (int i = 0; i < VEC; ++i) x[i] = v[i];
-    __builtin_nontemporal_store(x, reinterpret_cast<vec_t *>(p));
+    if (stream)
+        __builtin_nontemporal_store(x, reinterpret_cast<vec_t *>(p));
+    else
+        *reinterpret_cast<vec_t *>(p) = x;
 }
-__device__ __forceinline__ void store_vec(float *p, const float (&v)[1]) { __builtin_nontemporal_store(v[0], p); }
+__device__ __forceinline__ void store_vec(float *p, const float (&v)[1], bool stream)
+{
+    if (stream)
+        __builtin_nontemporal_store(v[0], p);
+    else
+        *p = v[0];
+}
 
 __device__ __forceinline__ uint32_t pack_signs(const Seg &g) { return (g.sA >> 31) | ((g.sM >> 31) << 1); }
 __device__ __forceinline__ void unpack_signs(uint32_t s, Seg &g)
@@ -357,7 +369,7 @@ __global__ __launch_bounds__(NW * 64, MINW) void heinsen_scan_bnd(BndParams p)
             for (int v = 0; v < VEC; ++v) o[v] = Av[k][v] + Mv[k][v];
         }
 #endif
-        if (full || (chan_ok && t0 + k < p.n)) store_vec(op + (int64_t)k * p.D + loff, o);
+        if (full || (chan_ok && t0 + k < p.n)) store_vec(op + (int64_t)k * p.D + loff, o, p.stream_out != 0);
         if (SB) __builtin_amdgcn_sched_barrier(0);
     }
     HS_STAMP(7);
@@ -368,6 +380,9 @@ __global__ __launch_bounds__(NW * 64, MINW) void heinsen_scan_bnd(BndParams p)
 #ifdef HS_TRACE
 unsigned long long *g_trace = nullptr;
 #endif
+
+// MI355X: 256 MB of memory-side cache; an output up to three quarters of it is left to be cached
+constexpr int64_t kLastLevelCacheBytes = 192ll << 20;
 
 struct BndPlan {
     int vec, T, NW, G, CH, variant;
@@ -445,6 +460,7 @@ hipError_t launch_mode(const ScanCall &c, const BndPlan &pl, rec_t *records, Lau
     p.D = c.D;
     p.n = c.n;
     p.x0_stride = c.x0_scalar ? 0 : 1;
+    p.stream_out = (c.B * c.D * c.n * 4 > kLastLevelCacheBytes) ? 1 : 0;
     p.cols_per_b = pl.cols_per_b;
     p.ncols = pl.ncols;
     p.nchunks = pl.nchunks;
