@@ -286,6 +286,7 @@ struct TileParams {
     int64_t rows, n;
     int x0_stride;
     uint32_t tpr;          // tiles per row
+    uint32_t ntiles;       // rows * tpr
     uint32_t epoch;
     uint32_t ticket_base;
     rec_t *ticket;
@@ -357,6 +358,9 @@ __global__ __launch_bounds__(kTileWaves * 64) void heinsen_scan_tiles(TileParams
                                             __HIP_MEMORY_SCOPE_AGENT) - p.ticket_base;
         __syncthreads();
         tile = __builtin_amdgcn_readfirstlane(s_tile);
+        // a ticket outside the launch means the counter and the host's record of it have come apart
+        // (an earlier launch on this stream died): touch nothing rather than index out of bounds
+        if (tile >= p.ntiles) return;
     }
     HS_STAMP(0);
     const int64_t row = tile / p.tpr;
@@ -610,6 +614,7 @@ hipError_t launch_mode(const ScanCall &c, const BdnPlan &pl, rec_t *records, Lau
     p.n = c.n;
     p.x0_stride = c.x0_scalar ? 0 : 1;
     p.tpr = pl.tpr;
+    p.ntiles = pl.ntiles;
     p.epoch = tag.epoch;
     p.ticket_base = tag.ticket_base;
     p.ticket = records;

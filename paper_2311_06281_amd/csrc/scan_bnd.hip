@@ -29,6 +29,7 @@ struct BndParams {
     int cols_per_b;   // ceil(D / CH)
     int ncols;        // B * cols_per_b
     int nchunks;      // ceil(n / (NW*T))
+    uint32_t ntiles;  // ncols * nchunks
     uint32_t epoch;
     uint32_t ticket_base;
     rec_t *ticket;    // word 0 of the record buffer
@@ -40,7 +41,7 @@ struct BndParams {
 #ifdef HS_TUNING
     uint32_t stagger_lo, stagger_hi;
     int stagger_ticks;
-    int ablate; // bit0: no waiting for carries, bit1: no arithmetic, bit2: tile = blockIdx (no ticket)
+    int ablate; // bit0: no waiting for carries, bit1: no arithmetic
 #endif
 };
 
@@ -120,16 +121,14 @@ __global__ __launch_bounds__(NW * 64, MINW) void heinsen_scan_bnd(BndParams p)
 
     // Tiles are handed out in start order, so every tile a workgroup may wait for (same column,
     // earlier chunk => smaller ticket) belongs to a workgroup that is already running.
-#ifdef HS_TUNING
-    if (p.ablate & 4) {
-        if (threadIdx.x == 0) s_tile = blockIdx.x;
-    } else
-#endif
     if (threadIdx.x == 0)
         s_tile = __hip_atomic_fetch_add(reinterpret_cast<uint32_t *>(p.ticket), 1u, __ATOMIC_RELAXED,
                                         __HIP_MEMORY_SCOPE_AGENT) - p.ticket_base;
     __syncthreads();
     const uint32_t tile = __builtin_amdgcn_readfirstlane(s_tile);
+    // A ticket outside the launch can only mean that the counter and the host's record of it have come
+    // apart (an earlier launch on this stream died): touch nothing rather than index out of bounds.
+    if (tile >= p.ntiles) return;
 #ifdef HS_TUNING
     if (p.stagger_ticks > 0 && tile >= p.stagger_lo && tile < p.stagger_hi) {
         const unsigned long long t_start = wall_clock64();
@@ -464,6 +463,7 @@ hipError_t launch_mode(const ScanCall &c, const BndPlan &pl, rec_t *records, Lau
     p.cols_per_b = pl.cols_per_b;
     p.ncols = pl.ncols;
     p.nchunks = pl.nchunks;
+    p.ntiles = pl.ntiles;
     p.epoch = tag.epoch;
     p.ticket_base = tag.ticket_base;
     p.ticket = records;
