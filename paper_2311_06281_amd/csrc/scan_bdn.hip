@@ -395,8 +395,9 @@ __global__ __launch_bounds__(kTileWaves * 64) void heinsen_scan_tiles(TileParams
     uint64_t have = 0;
     if (MULTI && w == 0) have = fetch_records();
 
-    // global <-> lane traffic of each wave goes through its own LDS region (coalesced both ways)
-    __shared__ u32x4 stage[VECIO ? NW : 1][VECIO ? 64 * (ITEMS / 4 + 1) : 1];
+    // global <-> lane traffic of each wave goes through its own LDS region (coalesced both ways); the pad
+    // slot after the last lane is never used, and leaving it out lets four workgroups share a CU
+    __shared__ u32x4 stage[VECIO ? NW : 1][VECIO ? 64 * (ITEMS / 4 + 1) - 1 : 1];
     const int64_t wstart = (int64_t)c * kTile + (int64_t)w * (64 * ITEMS); // first element of this wave
     float Av[ITEMS], Mv[ITEMS];
     uint32_t sw;
