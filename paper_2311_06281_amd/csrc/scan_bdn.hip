@@ -14,6 +14,7 @@
 // arithmetic is in heinsen_math.hpp.
 #include "heinsen_internal.hpp"
 #include "heinsen_math.hpp"
+#include <cstdlib>
 
 namespace hs {
 #ifdef HS_TRACE
@@ -275,7 +276,7 @@ __global__ __launch_bounds__(256, VECIO ? 4 : 1) void heinsen_scan_rows_wave(Row
 // form a chain, n / (4096 * tile) links long.
 
 constexpr int kTileWaves = 8;   // waves per workgroup
-constexpr int kTileItems = 16;  // elements per lane
+constexpr int kTileItems = 32;  // elements per lane
 constexpr int kTile = kTileWaves * 64 * kTileItems;
 
 struct TileParams {
@@ -292,6 +293,9 @@ struct TileParams {
     rec_t *ticket;
     rec_t *recs;           // per row: level-1, level-2, level-3 summaries (2 records each), states (2 records each)
     uint32_t off2, off3, off4, row_stride; // record offsets of levels 2, 3 and the states inside a row's block
+#ifdef HS_TUNING
+    int ablate; // development: bit0 do not wait for carries (wrong results), bit1 no arithmetic
+#endif
 #ifdef HS_TRACE
     unsigned long long *trace;
 #endif
@@ -417,7 +421,13 @@ __global__ __launch_bounds__(kTileWaves * 64) void heinsen_scan_tiles(TileParams
     } else {
         lane_load<LOG_IN, InT, ITEMS, false>(arow, brow, start, p.n, Av, Mv);
     }
+#ifdef HS_TUNING
+    Seg mine = seg_identity();
+    sw = 0;
+    if (!(p.ablate & 2)) mine = lane_scan<SIGNED, LOG_IN, LOG_OUT, ITEMS>(Av, Mv, sw);
+#else
     Seg mine = lane_scan<SIGNED, LOG_IN, LOG_OUT, ITEMS>(Av, Mv, sw);
+#endif
     Seg incl = wave_inclusive_scan<SIGNED>(mine);
     Seg lane_excl = wave_shift_up<SIGNED>(incl);
     HS_STAMP(1);
@@ -460,6 +470,9 @@ __global__ __launch_bounds__(kTileWaves * 64) void heinsen_scan_tiles(TileParams
             bool pub2 = !lead2, pub3 = !lead3;
             Seg f1 = seg_identity(), f2 = seg_identity(), f3 = seg_identity(), a2 = seg_identity();
             const uint64_t m1 = 0x0000ffff00000000ull, m2 = 0x00000000ffff0000ull, all = ~0ull;
+#ifdef HS_TUNING
+            if (p.ablate & 1) have = all;
+#endif
             for (;;) {
                 if ((!pub2 && (have & m1) == m1) || (!pub3 && (have & (m1 | m2)) == (m1 | m2)) || have == all) {
                     Seg part = (need && got && lane < 48) ? seg_from<SIGNED>(ra, rm) : seg_identity();
@@ -527,7 +540,12 @@ __global__ __launch_bounds__(kTileWaves * 64) void heinsen_scan_tiles(TileParams
         for (int qv = 0; qv < NVO; ++qv)
 #pragma unroll
             for (int i = 0; i < 4; ++i)
+#ifdef HS_TUNING
+                vo[qv][i] = (p.ablate & 2) ? f2u(Av[qv * 4 + i] + Mv[qv * 4 + i])
+                                           : f2u(emit<SIGNED, LOG_OUT>(st, Av[qv * 4 + i], Mv[qv * 4 + i], swx, qv * 4 + i));
+#else
                 vo[qv][i] = f2u(emit<SIGNED, LOG_OUT>(st, Av[qv * 4 + i], Mv[qv * 4 + i], swx, qv * 4 + i));
+#endif
         int64_t n_vec = (p.n - wstart) / 4;
         n_vec = n_vec < 0 ? 0 : n_vec;
         wave_store_blocked<NVO>(reinterpret_cast<u32x4 *>(p.out + row * p.n + wstart), n_vec, stage[w], lane, vo);
@@ -624,6 +642,9 @@ hipError_t launch_mode(const ScanCall &c, const BdnPlan &pl, rec_t *records, Lau
     p.off3 = pl.off3;
     p.off4 = pl.off4;
     p.row_stride = pl.row_stride;
+#ifdef HS_TUNING
+    p.ablate = getenv("HEINSEN_ABLATE") ? atoi(getenv("HEINSEN_ABLATE")) : 0;
+#endif
 #ifdef HS_TRACE
     if (!g_trace_bdn) (void)hipMalloc(&g_trace_bdn, (size_t)(1u << 20) * 8 * sizeof(unsigned long long));
     p.trace = g_trace_bdn;

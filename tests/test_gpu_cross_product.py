@@ -51,7 +51,7 @@ MODES = {
     "log_logout": ("LOG_INPUTS", "LOG_OUTPUT"),
 }
 SHAPES = {
-    "BDN": [(2, 3, 1), (1, 5, 17), (2, 3, 520), (1, 2, 2048), (1, 3, 2056), (1, 1, 8192 * 3 + 8), (3, 2, 8192 + 1)],
+    "BDN": [(2, 3, 1), (1, 5, 17), (2, 3, 520), (1, 2, 2048), (1, 3, 2056), (1, 1, 16384 * 3 + 8), (3, 2, 16384 + 1)],
     "BND": [(2, 1, 5), (1, 17, 3), (2, 300, 64), (1, 257, 66), (1, 513, 130), (1, 40, 1000), (2, 1025, 7)],
 }
 
@@ -120,7 +120,7 @@ def test_every_mode_layout_and_storage_type(gpu, layout, mode, bf16):
         _check(got, a, b, x0, layout, mode)
 
 
-@pytest.mark.parametrize("layout,shape", [("BDN", (2, 3, 2048)), ("BDN", (1, 2, 8192 * 2)), ("BND", (1, 300, 128)), ("BND", (2, 64, 66))])
+@pytest.mark.parametrize("layout,shape", [("BDN", (2, 3, 2048)), ("BDN", (1, 2, 16384 * 2 + 16)), ("BND", (1, 300, 128)), ("BND", (2, 64, 66))])
 @pytest.mark.parametrize("bf16", [False, True])
 @pytest.mark.parametrize("offset", [1, 2, 3])
 def test_pointers_that_are_only_element_aligned(gpu, layout, shape, bf16, offset):
@@ -139,8 +139,8 @@ def test_interleaved_shapes_on_one_stream_share_scratch_safely(gpu):
     torch, hb = gpu
     rng = np.random.default_rng(5)
     cases = []
-    for layout, shape in (("BND", (1, 1030, 130)), ("BDN", (1, 2, 8192 * 5 + 4)), ("BND", (2, 520, 64)),
-                          ("BDN", (2, 1, 8192 * 2)), ("BND", (1, 2100, 70))):
+    for layout, shape in (("BND", (1, 1030, 130)), ("BDN", (1, 2, 16384 * 5 + 4)), ("BND", (2, 520, 64)),
+                          ("BDN", (2, 1, 16384 * 2 + 4)), ("BND", (1, 2100, 70))):
         a, b, x0 = _inputs(rng, shape, layout, "signed")
         cases.append((layout, shape, a, b, x0))
     order = [0, 1, 2, 3, 4, 1, 0, 3, 2, 4, 4, 0, 1]

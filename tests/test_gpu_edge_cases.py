@@ -52,7 +52,7 @@ def _assert_signed(got, ref, layout):
     assert np.all(np.abs(got - ref) <= bound + 1e-30), float(np.max(np.abs(got - ref) / (bound + 1e-30)))
 
 
-SHAPES = [("BDN", (2, 3, 700)), ("BDN", (1, 2, 9000)), ("BDN", (1, 1, 30000)), ("BND", (2, 900, 70)), ("BND", (1, 300, 130))]
+SHAPES = [("BDN", (2, 3, 700)), ("BDN", (1, 2, 9000)), ("BDN", (1, 1, 50000)), ("BND", (2, 900, 70)), ("BND", (1, 300, 130))]
 
 
 @pytest.mark.parametrize("layout,shape", SHAPES)
@@ -185,7 +185,7 @@ def test_output_may_alias_an_input(gpu, layout, shape):
     assert np.array_equal(plain.view(np.uint32), on_b.view(np.uint32))
 
 
-@pytest.mark.parametrize("layout,shape,k", [("BDN", (1, 2, 20000), 8191), ("BDN", (1, 2, 20000), 8192), ("BDN", (2, 2, 1500), 777),
+@pytest.mark.parametrize("layout,shape,k", [("BDN", (1, 2, 40000), 16383), ("BDN", (1, 2, 40000), 16384), ("BDN", (2, 2, 1500), 777),
                                             ("BND", (1, 1000, 70), 255), ("BND", (1, 1000, 70), 256), ("BND", (1, 1000, 70), 513)])
 def test_scan_by_parts_equals_scan_in_one_go(gpu, layout, shape, k):
     # Sec. 1 footnote: prefix sums can be computed by parts -- restart from x_k and continue
@@ -279,7 +279,7 @@ def test_channels_do_not_interact(gpu):
 
 def test_two_streams_use_separate_scratch(gpu):
     torch, hb = gpu
-    cfgs = [workloads.CONFIGS[5].scaled(B=2, D=256, n=4096), workloads.CONFIGS[3].scaled(n=8192 * 40)]
+    cfgs = [workloads.CONFIGS[5].scaled(B=2, D=256, n=4096), workloads.CONFIGS[3].scaled(n=16384 * 40)]
     singles = []
     for cfg in cfgs:
         from parity import run_gpu

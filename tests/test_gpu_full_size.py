@@ -74,3 +74,22 @@ def test_full_size_repeated_items(gpu, idx, distinct):
     nbad, worst = violations(sub, got, ref)
     print(f"[full] cfg{idx}: worst error/bound {worst:.3g}", flush=True)
     assert nbad == 0, f"{nbad} of {ref.size} outside the tolerance (worst {worst:.3g})"
+
+
+def test_longer_than_one_super_block(gpu):
+    """One sequence a little longer than 4096 tiles: the float64 state handed from one super-block of
+    tiles to the next is the only carry that forms a chain, and only such lengths exercise it."""
+    torch, hb = gpu
+    import bench
+
+    cfg = workloads.CONFIGS[3].scaled(n=(1 << 26) + 16384 * 3 + 5)
+    print(f"[full] cfg3 distribution, n={cfg.n}", flush=True)
+    a, b, x0, out = bench.device_inputs(cfg, torch, distinct=1)
+    hb.heinsen_scan(a, b, x0, out, cfg.B, cfg.D, cfg.n, hb.LAYOUTS[cfg.layout], hb.flags_from_names(cfg.flags),
+                    torch.cuda.current_stream())
+    torch.cuda.synchronize()
+    got = out.cpu().numpy()
+    ref = reference(cfg, workloads.generate(cfg), threads=1)
+    nbad, worst = violations(cfg, got, ref)
+    print(f"[full] worst error/bound {worst:.3g}", flush=True)
+    assert nbad == 0

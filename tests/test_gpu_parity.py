@@ -38,7 +38,7 @@ def test_cfg1_single_sequence(gpu):
     _check(workloads.CONFIGS[1], gpu, "cfg1")
 
 
-@pytest.mark.parametrize("n", [1, 2, 63, 64, 65, 511, 512, 513, 1000, 2047, 2048, 2049, 4095, 4097, 9000])
+@pytest.mark.parametrize("n", [1, 2, 63, 64, 65, 511, 512, 513, 1000, 2047, 2048, 2049, 4095, 4097, 9000, 16383, 16385, 40000])
 def test_cfg1_lengths(gpu, n):
     _check(workloads.CONFIGS[1].scaled(n=n), gpu, f"cfg1 n={n}")
 
@@ -50,13 +50,13 @@ def test_cfg2_scaled(gpu, B, D, n):
 
 
 # ---- configuration 3: one long sequence (tiles chained through global memory) -------------------------------
-@pytest.mark.parametrize("n", [4096 * 3, 4096 * 300 + 8, 4096 * 520 + 1])
+@pytest.mark.parametrize("n", [16384 * 3, 16384 * 75 + 8, 16384 * 300 + 1])  # 3 tiles; 5 groups of 16; 2 blocks of 256
 def test_cfg3_scaled(gpu, n):
     _check(workloads.CONFIGS[3].scaled(n=n), gpu, f"cfg3 n={n}")
 
 
 # ---- configuration 4: bf16 logs in, log out, [B, D, n] --------------------------------------------------------
-@pytest.mark.parametrize("B,D,n", [(2, 64, 2048), (1, 33, 1000), (2, 5, 999), (1, 7, 100), (1, 3, 6000), (1, 2, 40000)])
+@pytest.mark.parametrize("B,D,n", [(2, 64, 2048), (1, 33, 1000), (2, 5, 999), (1, 7, 100), (1, 3, 6000), (1, 2, 40000), (1, 1, 16384 * 20 + 8)])
 def test_cfg4_scaled(gpu, B, D, n):
     _check(workloads.CONFIGS[4].scaled(B=B, D=D, n=n), gpu, f"cfg4 {B}x{D}x{n}")
 
@@ -70,14 +70,14 @@ def test_cfg5_scaled(gpu, B, D, n):
 def test_cfg5_distribution_in_sequence_contiguous_layout(gpu):
     # the signed path of the [B, D, n] kernels (no benchmark configuration exercises it)
     base = workloads.CONFIGS[5]
-    for D, n in ((4, 2048), (3, 777), (2, 4096 * 5 + 3)):
+    for D, n in ((4, 2048), (3, 777), (2, 16384 * 5 + 3)):
         cfg = workloads.Config(5, 2, D, n, "BDN", (), True, name="signed rows")
         _check(cfg, gpu, f"cfg5-as-rows {D}x{n}")
 
 
 def test_results_are_bit_reproducible(gpu):
     torch, hb = gpu
-    for cfg in (workloads.CONFIGS[5].scaled(B=2, D=256, n=4096), workloads.CONFIGS[3].scaled(n=4096 * 600)):
+    for cfg in (workloads.CONFIGS[5].scaled(B=2, D=256, n=4096), workloads.CONFIGS[3].scaled(n=16384 * 300)):
         batch = workloads.generate(cfg)
         first = run_gpu(cfg, batch, torch, hb)
         for _ in range(3):
