@@ -120,6 +120,57 @@ def cpu_baseline(cfg):
             "single_thread_value": best[1]}
 
 
+def fig1_sweep(torch, hb, runs=30):
+    """The paper's one experiment (Sec. 4, Fig. 1) on this GPU: time to compute n elements sequentially
+    relative to the parallel computation, one sequence, n = 2^4 .. 2^26, mean of `runs` runs per point
+    (fewer for the long sequential runs).  Inputs: the single-sequence workload (a ~ U(0.5,1),
+    b ~ U(0,1), x0 = 1).  Also timed: the float64 CPU oracle on one host thread."""
+    import math
+
+    import oracle
+    from paper_2311_06281_amd import workloads
+
+    base = workloads.CONFIGS[1]
+    stream = torch.cuda.current_stream()
+    flags = hb.flags_from_names(base.flags)
+    points = []
+    for lg in range(4, 27):
+        n = 1 << lg
+        cfg = base.scaled(n=n)
+        batch = workloads.generate(cfg)
+        a = torch.from_numpy(batch.a).cuda()
+        b = torch.from_numpy(batch.b).cuda()
+        x0 = torch.from_numpy(batch.x0).cuda()
+        out = torch.empty_like(a)
+
+        def timed(fn, reps):
+            fn()
+            torch.cuda.synchronize()
+            ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(reps)]
+            for s, e in ev:
+                s.record(stream)
+                fn()
+                e.record(stream)
+            torch.cuda.synchronize()
+            return sum(s.elapsed_time(e) for s, e in ev) / reps * 1e3  # microseconds
+
+        t_par = timed(lambda: hb.heinsen_scan(a, b, x0, out, 1, 1, n, hb.HEINSEN_LAYOUT_BDN, flags, stream), runs)
+        seq_reps = runs if lg <= 20 else (5 if lg <= 23 else 2)
+        t_seq = timed(lambda: hb.heinsen_sequential(a, b, x0, out, n, stream), seq_reps)
+        a64 = batch.a.reshape(-1).astype("float64")
+        b64 = batch.b.reshape(-1).astype("float64")
+        t_cpu = float("inf")
+        for _ in range(3):
+            t0 = time.perf_counter()
+            oracle.seq_f64(a64, b64, 1.0)
+            t_cpu = min(t_cpu, (time.perf_counter() - t0) * 1e6)
+        points.append({"n": n, "parallel_us": t_par, "sequential_gpu_us": t_seq, "sequential_cpu_us": t_cpu,
+                       "ratio_gpu": t_seq / t_par, "ratio_cpu": t_cpu / t_par, "n_over_log2n": n / math.log2(n),
+                       "sequential_runs": seq_reps})
+        del a, b, x0, out
+    return points
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -128,6 +179,8 @@ def main() -> int:
     ap.add_argument("--workload", type=int, default=2, help="benchmark configuration 1..5 (default 2)")
     ap.add_argument("--no-others", action="store_true", help="time only the headline workload")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
+    ap.add_argument("--fig1", action="store_true",
+                    help="instead of the benchmark, run the paper's sequential-vs-parallel sweep over n (Fig. 1)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run plain device copies of a known size (reference for rocprofv3 FETCH_SIZE/WRITE_SIZE)")
     args = ap.parse_args()
@@ -145,6 +198,11 @@ def main() -> int:
         return 3
     hb.load()  # no fallback: raises if the HIP library is missing
     torch.cuda.set_device(0)
+
+    if args.fig1:
+        print(json.dumps({"experiment": "time(sequential) / time(parallel) vs n, one sequence, one MI355X",
+                          "runs_per_point": 30, "points": fig1_sweep(torch, hb)}))
+        return 0
 
     if args.copy_calibration:
         # 5 plain copies of 2^25 float32 (128 MiB read + 128 MiB written each): the HBM byte counters of

@@ -113,6 +113,15 @@ int heinsen_release_scratch(void);
 int heinsen_kernel_name(int64_t B, int64_t D, int64_t n, int layout, uint32_t flags, char *buf,
                         int buflen);
 
+/*
+ * heinsen_sequential -- the baseline of the paper's experiment (Sec. 4, Fig. 1): ONE sequence computed
+ * one element after the other on the GPU, x_t = a_t x_{t-1} + b_t in float32 (Sec. 3), by a single lane.
+ * a, b, out: device, n float32 each; x0: device, one float32; out[t-1] = x_t.  Asynchronous on `stream`.
+ * It exists to be timed against heinsen_scan; it is not a fallback of anything.
+ * Returns a heinsen_status_t.
+ */
+int heinsen_sequential(const void *a, const void *b, const void *x0, void *out, int64_t n, void *stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -31,7 +31,7 @@ HEINSEN_ERR_ALLOC = 3
 HEINSEN_ERR_HIP = 4
 
 EXPORTS = ("heinsen_scan", "heinsen_status_string", "heinsen_last_hip_error", "heinsen_version",
-           "heinsen_release_scratch", "heinsen_kernel_name")
+           "heinsen_release_scratch", "heinsen_kernel_name", "heinsen_sequential")
 
 _lib = None
 
@@ -62,6 +62,8 @@ def load() -> ctypes.CDLL:
         lib.heinsen_release_scratch.restype = ci
         lib.heinsen_kernel_name.argtypes = [i64, i64, i64, ci, u32, ctypes.c_char_p, ci]
         lib.heinsen_kernel_name.restype = ci
+        lib.heinsen_sequential.argtypes = [vp, vp, vp, vp, i64, vp]
+        lib.heinsen_sequential.restype = ci
         _lib = lib
     return _lib
 
@@ -130,3 +132,10 @@ def heinsen_scan(a, b, x0, out, B: int, D: int, n: int, layout: int, flags: int,
         if st in (HEINSEN_ERR_HIP, HEINSEN_ERR_ALLOC):
             msg += f", hipError_t {heinsen_last_hip_error()}"
         raise HeinsenError(st, msg)
+
+
+def heinsen_sequential(a, b, x0, out, n: int, stream=None) -> None:
+    """One sequence, one element after the other, on the GPU (the baseline of the paper's Fig. 1)."""
+    st = int(load().heinsen_sequential(_addr(a), _addr(b), _addr(x0), _addr(out), int(n), _stream_handle(stream)))
+    if st != HEINSEN_OK:
+        raise HeinsenError(st, heinsen_status_string(st))

@@ -314,3 +314,18 @@ def test_call_under_graph_capture_is_refused(gpu):
         finally:
             g.capture_end()
     assert st == hb.HEINSEN_ERR_UNSUPPORTED
+
+
+def test_sequential_baseline_kernel_matches_the_definition(gpu):
+    torch, hb = gpu
+    for n in (1, 5, 1023, 1024, 1025, 5000):
+        cfg = workloads.CONFIGS[1].scaled(n=n)
+        batch = workloads.generate(cfg)
+        a = torch.from_numpy(batch.a).cuda()
+        b = torch.from_numpy(batch.b).cuda()
+        x0 = torch.from_numpy(batch.x0).cuda()
+        out = torch.full_like(a, float("nan"))
+        hb.heinsen_sequential(a, b, x0, out, n, torch.cuda.current_stream())
+        torch.cuda.synchronize()
+        ref = oracle.seq_f64(batch.a.reshape(-1), batch.b.reshape(-1), 1.0)
+        np.testing.assert_allclose(out.cpu().numpy().reshape(-1), ref, rtol=1e-4, atol=1e-6)
