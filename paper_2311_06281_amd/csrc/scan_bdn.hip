@@ -24,46 +24,23 @@ namespace {
 
 // ---- lane-level pieces shared by both kernels --------------------------------------------------------
 
-// Loads the lane's ITEMS consecutive inputs starting `start` elements into a row of length n.
-// Steps at or beyond n are replaced by a = 1, b = 0 (which leave the state unchanged).
-template <bool LOG_IN, typename InT, int ITEMS, bool VECIO>
+// Element-wise fallback for rows whose pointers or length do not allow 16-byte vectors: loads the
+// lane's ITEMS consecutive inputs starting `start` elements into a row of length n.  Steps at or
+// beyond n are replaced by a = 1, b = 0 (which leave the state unchanged).
+template <bool LOG_IN, typename InT, int ITEMS>
 __device__ __forceinline__ void lane_load(const InT *arow, const InT *brow, int64_t start, int64_t n,
                                           float (&Av)[ITEMS], float (&Mv)[ITEMS])
 {
     const float id_a = LOG_IN ? 0.0f : 1.0f;
     const float id_b = LOG_IN ? -INFINITY : 0.0f;
-    if (VECIO) {
-        constexpr int VL = 16 / (int)sizeof(InT);
-        static_assert(ITEMS % VL == 0, "ITEMS must be a multiple of the vector length");
-        typedef InT vec_t __attribute__((ext_vector_type(VL)));
 #pragma unroll
-        for (int j = 0; j < ITEMS / VL; ++j) {
-            if (start + j * VL < n) { // n is a multiple of VL: a vector is all in or all out
-                vec_t va = *reinterpret_cast<const vec_t *>(arow + start + j * VL);
-                vec_t vb = *reinterpret_cast<const vec_t *>(brow + start + j * VL);
-#pragma unroll
-                for (int i = 0; i < VL; ++i) {
-                    Av[j * VL + i] = widen(va[i]);
-                    Mv[j * VL + i] = widen(vb[i]);
-                }
-            } else {
-#pragma unroll
-                for (int i = 0; i < VL; ++i) {
-                    Av[j * VL + i] = id_a;
-                    Mv[j * VL + i] = id_b;
-                }
-            }
-        }
-    } else {
-#pragma unroll
-        for (int k = 0; k < ITEMS; ++k) {
-            if (start + k < n) {
-                Av[k] = widen(arow[start + k]);
-                Mv[k] = widen(brow[start + k]);
-            } else {
-                Av[k] = id_a;
-                Mv[k] = id_b;
-            }
+    for (int k = 0; k < ITEMS; ++k) {
+        if (start + k < n) {
+            Av[k] = widen(arow[start + k]);
+            Mv[k] = widen(brow[start + k]);
+        } else {
+            Av[k] = id_a;
+            Mv[k] = id_b;
         }
     }
 }
@@ -95,32 +72,16 @@ __device__ __forceinline__ Seg lane_scan(float (&Av)[ITEMS], float (&Mv)[ITEMS],
     return run;
 }
 
-// Emits the lane's elements given the state at the lane's first step.
-template <bool SIGNED, bool LOG_OUT, int ITEMS, bool VECIO>
+// Element-wise fallback: emits the lane's elements given the state at the lane's first step.
+template <bool SIGNED, bool LOG_OUT, int ITEMS>
 __device__ __forceinline__ void lane_emit(float *orow, int64_t start, int64_t n, const State &st,
                                           const float (&Av)[ITEMS], const float (&Mv)[ITEMS], uint32_t sw)
 {
-    float o[ITEMS];
     const uint32_t swx = fold_state_sign<SIGNED>(sw, st);
 #pragma unroll
-    for (int k = 0; k < ITEMS; ++k) o[k] = emit<SIGNED, LOG_OUT>(st, Av[k], Mv[k], swx, k);
-    if (VECIO) {
-        typedef float vec_t __attribute__((ext_vector_type(4)));
-#pragma unroll
-        for (int j = 0; j < ITEMS / 4; ++j) {
-            if (start + j * 4 < n) {
-                vec_t v;
-                v[0] = o[j * 4 + 0];
-                v[1] = o[j * 4 + 1];
-                v[2] = o[j * 4 + 2];
-                v[3] = o[j * 4 + 3];
-                *reinterpret_cast<vec_t *>(orow + start + j * 4) = v;
-            }
-        }
-    } else {
-#pragma unroll
-        for (int k = 0; k < ITEMS; ++k)
-            if (start + k < n) orow[start + k] = o[k];
+    for (int k = 0; k < ITEMS; ++k) {
+        const float o = emit<SIGNED, LOG_OUT>(st, Av[k], Mv[k], swx, k);
+        if (start + k < n) orow[start + k] = o;
     }
 }
 
@@ -242,7 +203,7 @@ __global__ __launch_bounds__(256, VECIO ? 4 : 1) void heinsen_scan_rows_wave(Row
         unpack_inputs<InT, NVI, ITEMS>(va, Av);
         unpack_inputs<InT, NVI, ITEMS>(vb, Mv);
     } else {
-        lane_load<LOG_IN, InT, ITEMS, false>(arow, brow, start, p.n, Av, Mv);
+        lane_load<LOG_IN, InT, ITEMS>(arow, brow, start, p.n, Av, Mv);
     }
     Seg mine = lane_scan<SIGNED, LOG_IN, LOG_OUT, ITEMS>(Av, Mv, sw);
     Seg excl = wave_shift_up<SIGNED>(wave_inclusive_scan<SIGNED>(mine));
@@ -261,7 +222,7 @@ __global__ __launch_bounds__(256, VECIO ? 4 : 1) void heinsen_scan_rows_wave(Row
                 vo[q][i] = f2u(emit<SIGNED, LOG_OUT>(st, Av[q * 4 + i], Mv[q * 4 + i], swx, q * 4 + i));
         wave_store_blocked<NVO>(reinterpret_cast<u32x4 *>(orow), p.n / 4, stage[w], lane, vo);
     } else {
-        lane_emit<SIGNED, LOG_OUT, ITEMS, false>(orow, start, p.n, st, Av, Mv, sw);
+        lane_emit<SIGNED, LOG_OUT, ITEMS>(orow, start, p.n, st, Av, Mv, sw);
     }
 }
 
@@ -293,9 +254,6 @@ struct TileParams {
     rec_t *ticket;
     rec_t *recs;           // per row: level-1, level-2, level-3 summaries (2 records each), states (2 records each)
     uint32_t off2, off3, off4, row_stride; // record offsets of levels 2, 3 and the states inside a row's block
-#ifdef HS_TUNING
-    int ablate; // development: bit0 do not wait for carries (wrong results), bit1 no arithmetic
-#endif
 #ifdef HS_TRACE
     unsigned long long *trace;
 #endif
@@ -419,15 +377,9 @@ __global__ __launch_bounds__(kTileWaves * 64) void heinsen_scan_tiles(TileParams
         unpack_inputs<InT, NVI, ITEMS>(va, Av);
         unpack_inputs<InT, NVI, ITEMS>(vb, Mv);
     } else {
-        lane_load<LOG_IN, InT, ITEMS, false>(arow, brow, start, p.n, Av, Mv);
+        lane_load<LOG_IN, InT, ITEMS>(arow, brow, start, p.n, Av, Mv);
     }
-#ifdef HS_TUNING
-    Seg mine = seg_identity();
-    sw = 0;
-    if (!(p.ablate & 2)) mine = lane_scan<SIGNED, LOG_IN, LOG_OUT, ITEMS>(Av, Mv, sw);
-#else
     Seg mine = lane_scan<SIGNED, LOG_IN, LOG_OUT, ITEMS>(Av, Mv, sw);
-#endif
     Seg incl = wave_inclusive_scan<SIGNED>(mine);
     Seg lane_excl = wave_shift_up<SIGNED>(incl);
     HS_STAMP(1);
@@ -470,9 +422,6 @@ __global__ __launch_bounds__(kTileWaves * 64) void heinsen_scan_tiles(TileParams
             bool pub2 = !lead2, pub3 = !lead3;
             Seg f1 = seg_identity(), f2 = seg_identity(), f3 = seg_identity(), a2 = seg_identity();
             const uint64_t m1 = 0x0000ffff00000000ull, m2 = 0x00000000ffff0000ull, all = ~0ull;
-#ifdef HS_TUNING
-            if (p.ablate & 1) have = all;
-#endif
             for (;;) {
                 if ((!pub2 && (have & m1) == m1) || (!pub3 && (have & (m1 | m2)) == (m1 | m2)) || have == all) {
                     Seg part = (need && got && lane < 48) ? seg_from<SIGNED>(ra, rm) : seg_identity();
@@ -540,17 +489,12 @@ __global__ __launch_bounds__(kTileWaves * 64) void heinsen_scan_tiles(TileParams
         for (int qv = 0; qv < NVO; ++qv)
 #pragma unroll
             for (int i = 0; i < 4; ++i)
-#ifdef HS_TUNING
-                vo[qv][i] = (p.ablate & 2) ? f2u(Av[qv * 4 + i] + Mv[qv * 4 + i])
-                                           : f2u(emit<SIGNED, LOG_OUT>(st, Av[qv * 4 + i], Mv[qv * 4 + i], swx, qv * 4 + i));
-#else
                 vo[qv][i] = f2u(emit<SIGNED, LOG_OUT>(st, Av[qv * 4 + i], Mv[qv * 4 + i], swx, qv * 4 + i));
-#endif
         int64_t n_vec = (p.n - wstart) / 4;
         n_vec = n_vec < 0 ? 0 : n_vec;
         wave_store_blocked<NVO>(reinterpret_cast<u32x4 *>(p.out + row * p.n + wstart), n_vec, stage[w], lane, vo);
     } else {
-        lane_emit<SIGNED, LOG_OUT, ITEMS, false>(p.out + row * p.n, start, p.n, st, Av, Mv, sw);
+        lane_emit<SIGNED, LOG_OUT, ITEMS>(p.out + row * p.n, start, p.n, st, Av, Mv, sw);
     }
     HS_STAMP(6);
     HS_STAMP(7);
@@ -642,9 +586,6 @@ hipError_t launch_mode(const ScanCall &c, const BdnPlan &pl, rec_t *records, Lau
     p.off3 = pl.off3;
     p.off4 = pl.off4;
     p.row_stride = pl.row_stride;
-#ifdef HS_TUNING
-    p.ablate = getenv("HEINSEN_ABLATE") ? atoi(getenv("HEINSEN_ABLATE")) : 0;
-#endif
 #ifdef HS_TRACE
     if (!g_trace_bdn) (void)hipMalloc(&g_trace_bdn, (size_t)(1u << 20) * 8 * sizeof(unsigned long long));
     p.trace = g_trace_bdn;

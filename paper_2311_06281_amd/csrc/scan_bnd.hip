@@ -38,11 +38,6 @@ struct BndParams {
 #ifdef HS_TRACE
     unsigned long long *trace; // [ntiles][8] wall-clock stamps of wave 0 (100 MHz), development only
 #endif
-#ifdef HS_TUNING
-    uint32_t stagger_lo, stagger_hi;
-    int stagger_ticks;
-    int ablate; // bit0: no waiting for carries, bit1: no arithmetic
-#endif
 };
 
 #ifdef HS_TRACE
@@ -129,12 +124,6 @@ __global__ __launch_bounds__(NW * 64, MINW) void heinsen_scan_bnd(BndParams p)
     // A ticket outside the launch can only mean that the counter and the host's record of it have come
     // apart (an earlier launch on this stream died): touch nothing rather than index out of bounds.
     if (tile >= p.ntiles) return;
-#ifdef HS_TUNING
-    if (p.stagger_ticks > 0 && tile >= p.stagger_lo && tile < p.stagger_hi) {
-        const unsigned long long t_start = wall_clock64();
-        while (wall_clock64() - t_start < (unsigned long long)p.stagger_ticks) __builtin_amdgcn_s_sleep(32);
-    }
-#endif
     HS_STAMP(0);
     const int chunk = (int)(tile / (uint32_t)p.ncols);
     const int col = (int)(tile % (uint32_t)p.ncols);
@@ -218,9 +207,6 @@ __global__ __launch_bounds__(NW * 64, MINW) void heinsen_scan_bnd(BndParams p)
         }
     }
 
-#ifdef HS_TUNING
-    if (p.ablate & 1) have_records = true; else
-#endif
     if (w == 0) have_records = records_in(); // first look: answered while the tile's loads were in flight
 
     // ---- encode + serial scan in each lane; Av/Mv become the per-element records (see stash) --------
@@ -228,9 +214,6 @@ __global__ __launch_bounds__(NW * 64, MINW) void heinsen_scan_bnd(BndParams p)
     Seg run[VEC];
 #pragma unroll
     for (int v = 0; v < VEC; ++v) sw[v] = 0u;
-#ifdef HS_TUNING
-    if (!(p.ablate & 2))
-#endif
 #pragma unroll
     for (int k = 0; k < T; ++k) {
 #pragma unroll
@@ -362,12 +345,6 @@ __global__ __launch_bounds__(NW * 64, MINW) void heinsen_scan_bnd(BndParams p)
         float o[VEC];
 #pragma unroll
         for (int v = 0; v < VEC; ++v) o[v] = emit<SIGNED, LOG_OUT>(st[v], Av[k][v], Mv[k][v], swx[v], k);
-#ifdef HS_TUNING
-        if (p.ablate & 2) {
-#pragma unroll
-            for (int v = 0; v < VEC; ++v) o[v] = Av[k][v] + Mv[k][v];
-        }
-#endif
         if (full || (chan_ok && t0 + k < p.n)) store_vec(op + (int64_t)k * p.D + loff, o, p.stream_out != 0);
         if (SB) __builtin_amdgcn_sched_barrier(0);
     }
@@ -469,12 +446,6 @@ hipError_t launch_mode(const ScanCall &c, const BndPlan &pl, rec_t *records, Lau
     p.ticket = records;
     p.agg = records + kRecordBase + pl.off_agg;
     p.state = records + kRecordBase + pl.off_state;
-#ifdef HS_TUNING
-    p.ablate = getenv("HEINSEN_ABLATE") ? atoi(getenv("HEINSEN_ABLATE")) : 0;
-    p.stagger_ticks = getenv("HEINSEN_STAGGER") ? atoi(getenv("HEINSEN_STAGGER")) : 0;
-    p.stagger_lo = getenv("HEINSEN_STAGGER_LO") ? atoi(getenv("HEINSEN_STAGGER_LO")) : 256;
-    p.stagger_hi = getenv("HEINSEN_STAGGER_HI") ? atoi(getenv("HEINSEN_STAGGER_HI")) : 512;
-#endif
 #ifdef HS_TRACE
     if (!g_trace) (void)hipMalloc(&g_trace, (size_t)(1u << 20) * 8 * sizeof(unsigned long long));
     p.trace = g_trace;
