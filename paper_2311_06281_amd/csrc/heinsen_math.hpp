@@ -203,6 +203,16 @@ __device__ __forceinline__ Seg row16_inclusive_scan(Seg g)
     return g;
 }
 
+// Inclusive scan inside each half of the wave (5 steps): lanes 31 and 63 end up with the fold of lanes
+// 0..31 and 32..63, in lane order.
+template <bool SIGNED>
+__device__ __forceinline__ Seg half_inclusive_scan(Seg g)
+{
+    g = row16_inclusive_scan<SIGNED>(g);
+    g = seg_combine<SIGNED>(seg_dpp<0x142, 0xa, SIGNED>(g), g); // row_bcast:15 into rows 1,3
+    return g;
+}
+
 template <bool SIGNED>
 __device__ __forceinline__ Seg seg_readlane(const Seg &g, int lane)
 {

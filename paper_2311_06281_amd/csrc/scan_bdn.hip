@@ -228,13 +228,13 @@ __global__ __launch_bounds__(256, VECIO ? 4 : 1) void heinsen_scan_rows_wave(Row
 
 // ---- tiles with a chained carry ------------------------------------------------------------------------
 //
-// Tile index c inside a row is read in base 16: c = ((s*16 + q)*16 + g)*16 + r.  Summaries are published
-// at three levels -- a tile's own (level 1), the 16 tiles of a group folded by its last tile (level 2),
-// the 16 groups of a block folded by the block's last tile (level 3) -- and the state at the start of
-// every 4096-tile super-block s, in float64, by the last tile of the previous one.  A tile therefore
-// reads at most 15 + 15 + 15 summaries and one state, all in one round of loads (one per lane of wave
-// 0), and folds them in a fixed order: results do not depend on timing.  Only the super-block states
-// form a chain, n / (4096 * tile) links long.
+// Tile index c inside a row is read in base 32: c = (s*32 + g)*32 + r.  Summaries are published at two
+// levels -- a tile's own (level 1) and the 32 tiles of a group folded by its last tile (level 2) -- and
+// the state at the start of every 1024-tile super-block s, in float64, by the last tile of the previous
+// one.  A tile therefore reads at most 31 + 31 summaries and one state, all in one round of loads (one
+// per lane of wave 0), and folds them in a fixed order: results do not depend on timing.  A level-2
+// summary is published as soon as the level-1 summaries it is made of are in, so no tile waits for
+// another tile's wait; only the super-block states form a chain, n / (1024 * tile) links long.
 
 constexpr int kTileWaves = 8;   // waves per workgroup
 constexpr int kTileItems = 32;  // elements per lane
@@ -252,8 +252,8 @@ struct TileParams {
     uint32_t epoch;
     uint32_t ticket_base;
     rec_t *ticket;
-    rec_t *recs;           // per row: level-1, level-2, level-3 summaries (2 records each), states (2 records each)
-    uint32_t off2, off3, off4, row_stride; // record offsets of levels 2, 3 and the states inside a row's block
+    rec_t *recs;           // per row: level-1 and level-2 summaries (2 records each), states (2 records each)
+    uint32_t off2, off4, row_stride; // record offsets of level 2 and of the states inside a row's block
 #ifdef HS_TRACE
     unsigned long long *trace;
 #endif
@@ -332,18 +332,19 @@ __global__ __launch_bounds__(kTileWaves * 64) void heinsen_scan_tiles(TileParams
     const int64_t start = (int64_t)c * kTile + (int64_t)threadIdx.x * ITEMS;
 
     // ---- wave 0 asks for the carry records it needs before the tile's own loads (see scan_bnd.hip) ---
-    const uint32_t r = c & 15u, g = (c >> 4) & 15u, q = (c >> 8) & 15u, sb = c >> 12;
+    const uint32_t r = c & 31u, g = (c >> 5) & 31u, sb = c >> 10;
     const bool more = c + 1 < p.tpr;
     rec_t *const rrow = p.recs + (size_t)row * p.row_stride;
     rec_t ra = 0, rm = 0;
     const rec_t *fp = nullptr;
     bool need = false;
     if (MULTI && w == 0) {
-        const int sub = lane & 15, lvl = lane >> 4; // lanes 0-15: level 3, 16-31: level 2, 32-47: level 1
-        if (lvl == 0 && (uint32_t)sub < q) { need = true; fp = rrow + p.off3 + 2 * (size_t)(((c >> 12) << 4) + sub); }
-        if (lvl == 1 && (uint32_t)sub < g) { need = true; fp = rrow + p.off2 + 2 * (size_t)(((c >> 8) << 4) + sub); }
-        if (lvl == 2 && (uint32_t)sub < r) { need = true; fp = rrow + 2 * (size_t)(((c >> 4) << 4) + sub); }
-        if (lane == 63 && sb > 0) { need = true; fp = rrow + p.off4 + 2 * (size_t)sb; }
+        // lanes 0-30: level 2 (earlier groups of the super-block), lane 31: the super-block state,
+        // lanes 32-62: level 1 (earlier tiles of the group)
+        const uint32_t sub = (uint32_t)lane & 31u;
+        if (lane < 31 && sub < g) { need = true; fp = rrow + p.off2 + 2 * (size_t)(((c >> 10) << 5) + sub); }
+        if (lane == 31 && sb > 0) { need = true; fp = rrow + p.off4 + 2 * (size_t)sb; }
+        if (lane >= 32 && lane < 63 && sub < r) { need = true; fp = rrow + 2 * (size_t)(((c >> 5) << 5) + sub); }
     }
     bool got = !need; // this lane's records are in
     auto fetch_records = [&]() -> uint64_t {
@@ -413,33 +414,24 @@ __global__ __launch_bounds__(kTileWaves * 64) void heinsen_scan_tiles(TileParams
         }
         HS_STAMP(2);
         if (MULTI) {
-            if (more && r < 15u && lane == 0) seg_put<SIGNED>(rrow + 2 * (size_t)c, rrow + 2 * (size_t)c + 1, total, p.epoch);
-            // Levels arrive independently and what this tile owes to later tiles is published as soon as
-            // its inputs are in: the group summary needs level 1 only, the block summary levels 1 and 2,
-            // so no tile ever waits for a chain of other tiles' waits.
-            const bool lead2 = more && r == 15u;            // folds its group of 16 tiles
-            const bool lead3 = lead2 && g == 15u;           // ... and its block of 16 groups
-            bool pub2 = !lead2, pub3 = !lead3;
-            Seg f1 = seg_identity(), f2 = seg_identity(), f3 = seg_identity(), a2 = seg_identity();
-            const uint64_t m1 = 0x0000ffff00000000ull, m2 = 0x00000000ffff0000ull, all = ~0ull;
+            if (more && r < 31u && lane == 0) seg_put<SIGNED>(rrow + 2 * (size_t)c, rrow + 2 * (size_t)c + 1, total, p.epoch);
+            // The last tile of a group owes the later groups the summary of its group; it needs level 1
+            // only and is published as soon as that is in, whatever else is still on its way.
+            const bool lead = more && r == 31u;
+            bool pub2 = !lead;
+            Seg f1 = seg_identity(), f2 = seg_identity(), a2 = seg_identity();
+            const uint64_t m1 = 0x7fffffff00000000ull, all = ~0ull;
             for (;;) {
-                if ((!pub2 && (have & m1) == m1) || (!pub3 && (have & (m1 | m2)) == (m1 | m2)) || have == all) {
-                    Seg part = (need && got && lane < 48) ? seg_from<SIGNED>(ra, rm) : seg_identity();
-                    part = row16_inclusive_scan<SIGNED>(part);
-                    f3 = seg_readlane<SIGNED>(part, 15);
+                if ((!pub2 && (have & m1) == m1) || have == all) {
+                    Seg part = (need && got && lane != 31) ? seg_from<SIGNED>(ra, rm) : seg_identity();
+                    part = half_inclusive_scan<SIGNED>(part);
                     f2 = seg_readlane<SIGNED>(part, 31);
-                    f1 = seg_readlane<SIGNED>(part, 47);
+                    f1 = seg_readlane<SIGNED>(part, 63);
                     if (!pub2) {
-                        a2 = seg_combine<SIGNED>(f1, total); // this group of 16 tiles
-                        if (g < 15u && lane == 0)
-                            seg_put<SIGNED>(rrow + p.off2 + 2 * (size_t)(c >> 4), rrow + p.off2 + 2 * (size_t)(c >> 4) + 1, a2, p.epoch);
+                        a2 = seg_combine<SIGNED>(f1, total); // this group of 32 tiles
+                        if (g < 31u && lane == 0)
+                            seg_put<SIGNED>(rrow + p.off2 + 2 * (size_t)(c >> 5), rrow + p.off2 + 2 * (size_t)(c >> 5) + 1, a2, p.epoch);
                         pub2 = true;
-                    }
-                    if (!pub3 && (have & (m1 | m2)) == (m1 | m2)) {
-                        const Seg a3 = seg_combine<SIGNED>(f2, a2); // this block of 256 tiles
-                        if (q < 15u && lane == 0)
-                            seg_put<SIGNED>(rrow + p.off3 + 2 * (size_t)(c >> 8), rrow + p.off3 + 2 * (size_t)(c >> 8) + 1, a3, p.epoch);
-                        pub3 = true;
                     }
                 }
                 if (have == all) break;
@@ -448,25 +440,24 @@ __global__ __launch_bounds__(kTileWaves * 64) void heinsen_scan_tiles(TileParams
             }
             HS_STAMP(3);
             if (sb > 0) {
-                // lane 63 holds the super-block state: payloads are the high and low word of the double,
+                // lane 31 holds the super-block state: payloads are the high and low word of the double,
                 // the sign rides in the user bits of the first record
-                const uint32_t hi = (uint32_t)__builtin_amdgcn_readlane((int)rec_payload(ra), 63);
-                const uint32_t lo = (uint32_t)__builtin_amdgcn_readlane((int)rec_payload(rm), 63);
-                const uint32_t sg = (uint32_t)__builtin_amdgcn_readlane((int)rec_bits(ra), 63);
+                const uint32_t hi = (uint32_t)__builtin_amdgcn_readlane((int)rec_payload(ra), 31);
+                const uint32_t lo = (uint32_t)__builtin_amdgcn_readlane((int)rec_payload(rm), 31);
+                const uint32_t sg = (uint32_t)__builtin_amdgcn_readlane((int)rec_bits(ra), 31);
                 st.lx = __longlong_as_double((long long)(((unsigned long long)hi << 32) | lo));
                 st.s = SIGNED ? (sg << 31) : 0u;
             }
-            const State64 st3 = seg_apply64<SIGNED>(st, f3); // state at the start of the 256-tile block
-            if (lead3 && q == 15u) {
-                const Seg a3 = seg_combine<SIGNED>(f2, a2);
-                const State64 nx = seg_apply64<SIGNED>(st3, a3); // start of the next super-block
+            const State64 st2 = seg_apply64<SIGNED>(st, f2); // state at the start of the group
+            if (lead && g == 31u) {
+                const State64 nx = seg_apply64<SIGNED>(st2, a2); // start of the next super-block
                 const unsigned long long bits = (unsigned long long)__double_as_longlong(nx.lx);
                 if (lane == 0) {
                     rec_put(rrow + p.off4 + 2 * (size_t)(sb + 1), (uint32_t)(bits >> 32), p.epoch, SIGNED ? (nx.s >> 31) : 0u);
                     rec_put(rrow + p.off4 + 2 * (size_t)(sb + 1) + 1, (uint32_t)bits, p.epoch, 0u);
                 }
             }
-            st = seg_apply64<SIGNED>(seg_apply64<SIGNED>(st3, f2), f1);
+            st = seg_apply64<SIGNED>(st2, f1);
         }
         HS_STAMP(4);
         if (lane == 0) {
@@ -511,7 +502,7 @@ struct BdnPlan {
     bool multi;
     int64_t rows;
     uint32_t tpr, ntiles;
-    uint32_t off2, off3, off4, row_stride;
+    uint32_t off2, off4, row_stride;
     size_t records;
 };
 
@@ -531,10 +522,9 @@ BdnPlan make_plan(const ScanCall &c)
     pl.ntiles = (uint32_t)(pl.rows * pl.tpr);
     pl.multi = pl.tpr > 1;
     if (!pl.multi) return pl;
-    const uint32_t n1 = pl.tpr, n2 = (pl.tpr + 15) / 16, n3 = (pl.tpr + 255) / 256, n4 = (pl.tpr + 4095) / 4096 + 1;
+    const uint32_t n1 = pl.tpr, n2 = (pl.tpr + 31) / 32, n4 = (pl.tpr + 1023) / 1024 + 1;
     pl.off2 = 2 * n1;
-    pl.off3 = pl.off2 + 2 * n2;
-    pl.off4 = pl.off3 + 2 * n3;
+    pl.off4 = pl.off2 + 2 * n2;
     pl.row_stride = pl.off4 + 2 * n4;
     pl.records = (size_t)pl.rows * pl.row_stride;
     return pl;
@@ -583,7 +573,6 @@ hipError_t launch_mode(const ScanCall &c, const BdnPlan &pl, rec_t *records, Lau
     p.ticket = records;
     p.recs = records ? records + kRecordBase : nullptr;
     p.off2 = pl.off2;
-    p.off3 = pl.off3;
     p.off4 = pl.off4;
     p.row_stride = pl.row_stride;
 #ifdef HS_TRACE
