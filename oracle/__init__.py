@@ -110,6 +110,16 @@ def sequential_log(log_a, log_b, log_x0, layout: int = LAYOUT_BDN, threads: int 
     return _batched(_load().oracle_sequential_log_f32in, log_a, log_b, log_x0, layout, threads)
 
 
+def sequential_clog(a, b, x0, layout: int = LAYOUT_BDN, threads: int = 1) -> np.ndarray:
+    """Complex logarithm of the recurrence on signed data (paper Sec. 1, last paragraph: the logarithm of a
+    negative number is complex): complex128 with real part log|x_t| and imaginary part pi where x_t < 0,
+    0 elsewhere (principal value), x_t from the definition in float64."""
+    x = sequential(a, b, x0, layout=layout, threads=threads)
+    with np.errstate(divide="ignore"):
+        re = np.log(np.abs(x))
+    return re + 1j * np.where(np.signbit(x), np.pi, 0.0)
+
+
 def lcse(z) -> np.ndarray:
     """LCSE(z) = log cumsum exp(z) on a complex128 vector (paper Sec. 4)."""
     z = np.ascontiguousarray(z, dtype=np.complex128)

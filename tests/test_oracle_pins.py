@@ -231,6 +231,42 @@ def test_closed_form_agrees_with_definition(idx):
         assert np.array_equal((k[big] % 2) == 1, r[big] < 0)
 
 
+def test_complex_log_closed_forms():
+    """Sec. 1, last paragraph.  b = 0, x_0 = 1: x_t = a^t, so log x_t = t log|a| + i pi [a < 0 and t odd]."""
+    n = 40
+    t = np.arange(1, n + 1)
+    for aval in (-1.0, -2.0, -0.5, 3.0):
+        a = np.full((1, 1, n), aval, dtype=np.float32)
+        b = np.zeros((1, 1, n), dtype=np.float32)
+        z = oracle.sequential_clog(a, b, np.ones(1, dtype=np.float32))[0, 0]
+        np.testing.assert_allclose(z.real, t * np.log(abs(aval)), rtol=0, atol=1e-12)
+        want_im = np.where((aval < 0) & (t % 2 == 1), np.pi, 0.0)
+        np.testing.assert_array_equal(z.imag, want_im)
+    # a = 0 and b = 0 give x_t = 0: log 0 = -inf
+    z = oracle.sequential_clog(np.zeros((1, 1, 3), np.float32), np.zeros((1, 1, 3), np.float32), np.ones(1, np.float32))
+    assert np.all(np.isneginf(z.real))
+
+
+@pytest.mark.parametrize("idx", [2, 5])
+def test_complex_log_agrees_with_closed_form_in_the_complex_domain(idx):
+    """The complex-log output of the definition equals Sec. 4's expression evaluated with complex
+    logarithms (imaginary parts compared modulo 2 pi, and only where x_t is not a cancellation residue)."""
+    cfg = workloads.CONFIGS[idx].scaled(**SMALL[idx])
+    batch = workloads.generate(cfg)
+    layout = oracle.LAYOUT_BND if cfg.layout == "BND" else oracle.LAYOUT_BDN
+    ref = oracle.sequential(batch.a, batch.b, batch.x0, layout=layout)
+    z = oracle.sequential_clog(batch.a, batch.b, batch.x0, layout=layout)
+    np.testing.assert_array_equal(np.exp(z.real) * np.cos(z.imag) < 0, ref < 0)
+    for bi, d, a, b, x0 in _channels(cfg, batch):
+        zr = z[bi, d] if cfg.layout == "BDN" else z[bi, :, d]
+        r = ref[bi, d] if cfg.layout == "BDN" else ref[bi, :, d]
+        _, logx = oracle.logspace(a, b, x0)
+        big = np.abs(r) > 1e-6 * np.maximum.accumulate(np.abs(r))
+        np.testing.assert_allclose(logx.real[big], zr.real[big], rtol=0, atol=1e-6)
+        dphi = (logx.imag[big] - zr.imag[big]) / (2 * np.pi)
+        np.testing.assert_allclose(dphi, np.rint(dphi), rtol=0, atol=1e-6)
+
+
 def test_log_domain_definition_matches_linear_definition():
     cfg = workloads.CONFIGS[4].scaled(B=2, D=4, n=256)
     batch = workloads.generate(cfg)
