@@ -38,19 +38,25 @@ enum {
     HEINSEN_LOG_INPUTS = 1u << 0, /* a, b, x0 hold natural logs log a_t, log b_t, log x_0 (all quantities
                                      positive; -inf encodes 0).  Eq. (2) then starts from these logs.  */
     HEINSEN_LOG_OUTPUT = 1u << 1, /* out receives log x_t (Eq. (1)) instead of x_t (Eq. (3)).  Needs a
-                                     positive domain: LOG_INPUTS or POSITIVE must also be set.          */
+                                     positive domain (LOG_INPUTS or POSITIVE also set) or OUT_COMPLEX.  */
     HEINSEN_IN_BF16    = 1u << 2, /* a and b are stored as bfloat16 (x0 and out stay float32).          */
     HEINSEN_POSITIVE   = 1u << 3, /* caller promises a_t > 0, b_t >= 0, x_0 >= 0: sign tracking skipped.
                                      With a negative input the result is unspecified but memory-safe.   */
-    HEINSEN_X0_SCALAR  = 1u << 4  /* x0 points to ONE float32 that is broadcast to all B*D sequences.    */
+    HEINSEN_X0_SCALAR  = 1u << 4, /* x0 points to ONE float32 that is broadcast to all B*D sequences.    */
+    HEINSEN_OUT_COMPLEX = 1u << 5 /* with LOG_OUTPUT on signed data: out holds B*D*n complex64 values
+                                     (re, im interleaved), the complex logarithm of x_t (Sec. 1, last
+                                     paragraph): re = log|x_t|, im = pi where x_t < 0, else 0; x_t = 0
+                                     gives re = -inf.  Signs are always tracked (POSITIVE is ignored).
+                                     Not available with LOG_INPUTS.                                     */
 };
 
 typedef enum {
     HEINSEN_OK = 0,
     HEINSEN_ERR_INVALID_ARG = 1, /* null pointer, non-positive size, size overflow, misaligned pointer,
                                     unknown layout or flag bit                                           */
-    HEINSEN_ERR_UNSUPPORTED = 2, /* a legal but unimplemented combination: LOG_OUTPUT on a signed domain,
-                                    a call that needs scratch while its stream is being captured       */
+    HEINSEN_ERR_UNSUPPORTED = 2, /* a legal but unimplemented combination: LOG_OUTPUT on a signed domain
+                                    without OUT_COMPLEX, OUT_COMPLEX with LOG_INPUTS, a call that needs
+                                    scratch while its stream is being captured                         */
     HEINSEN_ERR_ALLOC = 3,       /* scratch memory could not be allocated; nothing was launched          */
     HEINSEN_ERR_HIP = 4          /* a HIP runtime call failed; see heinsen_last_hip_error()              */
 } heinsen_status_t;
@@ -62,7 +68,8 @@ typedef enum {
  *                            With LOG_INPUTS they hold natural logarithms.
  *   x0                     : device, B*D float32 indexed [b*D + d] (or 1 value with X0_SCALAR);
  *                            log x_0 with LOG_INPUTS.
- *   out                    : device, B*D*n float32 in `layout`; x_t, or log x_t with LOG_OUTPUT.
+ *   out                    : device, B*D*n float32 in `layout`; x_t, or log x_t with LOG_OUTPUT
+ *                            (B*D*n complex64, 8-byte aligned, with OUT_COMPLEX; no aliasing then).
  *                            May be exactly a_or_log_a or b_or_log_b when those are float32 (every tile
  *                            reads its inputs before it writes; "in situ", Sec. 1); any other overlap
  *                            is undefined.

@@ -14,6 +14,7 @@ lcse(z)                                       LCSE of Sec. 4 on a complex vector
 from __future__ import annotations
 
 import ctypes
+import math
 import os
 import subprocess
 
@@ -118,6 +119,30 @@ def sequential_clog(a, b, x0, layout: int = LAYOUT_BDN, threads: int = 1) -> np.
     with np.errstate(divide="ignore"):
         re = np.log(np.abs(x))
     return re + 1j * np.where(np.signbit(x), np.pi, 0.0)
+
+
+def seq_clog_scaled(a, b, x0: float) -> np.ndarray:
+    """Complex logarithm of one sequence whose values may leave the float64 range: the definition
+    x_t = a_t x_{t-1} + b_t with x carried as sign * exp(l), i.e. x_t = exp(l_{t-1}) (a_t sign + b_t exp(-l_{t-1})).
+    Pure Python, for short sequences.  Returns complex128 (log|x_t|, pi where x_t < 0)."""
+    a = np.asarray(a, dtype=np.float64)
+    b = np.asarray(b, dtype=np.float64)
+    n = a.shape[0]
+    out = np.empty(n, dtype=np.complex128)
+    x0 = float(x0)
+    l = math.log(abs(x0)) if x0 != 0.0 else -math.inf
+    sg = -1.0 if x0 < 0 else 1.0
+    for t in range(n):
+        if l == -math.inf:
+            y = b[t]
+            base = 0.0
+        else:
+            y = a[t] * sg + b[t] * math.exp(-l) if l > -700.0 else (a[t] * sg * math.exp(l) + b[t])
+            base = l if l > -700.0 else 0.0
+        l = base + math.log(abs(y)) if y != 0.0 else -math.inf
+        sg = -1.0 if y < 0 else 1.0
+        out[t] = complex(l, math.pi if y < 0 else 0.0)
+    return out
 
 
 def lcse(z) -> np.ndarray:

@@ -11,7 +11,8 @@
 namespace {
 
 constexpr uint32_t kAllFlags =
-    HEINSEN_LOG_INPUTS | HEINSEN_LOG_OUTPUT | HEINSEN_IN_BF16 | HEINSEN_POSITIVE | HEINSEN_X0_SCALAR;
+    HEINSEN_LOG_INPUTS | HEINSEN_LOG_OUTPUT | HEINSEN_IN_BF16 | HEINSEN_POSITIVE | HEINSEN_X0_SCALAR |
+    HEINSEN_OUT_COMPLEX;
 
 thread_local int t_last_hip_error = 0;
 
@@ -44,8 +45,12 @@ int describe(int64_t B, int64_t D, int64_t n, int layout, uint32_t flags, hs::Sc
     const int64_t lim = (int64_t)1 << 62;
     if (B > lim / D || B * D > lim / n || B * D * n >= lim) return HEINSEN_ERR_INVALID_ARG;
     const bool log_in = flags & HEINSEN_LOG_INPUTS;
-    const bool positive = (flags & HEINSEN_POSITIVE) || log_in;
-    if ((flags & HEINSEN_LOG_OUTPUT) && !positive) return HEINSEN_ERR_UNSUPPORTED;
+    const bool complex_out = flags & HEINSEN_OUT_COMPLEX;
+    if (complex_out && !(flags & HEINSEN_LOG_OUTPUT)) return HEINSEN_ERR_INVALID_ARG;
+    if (complex_out && log_in) return HEINSEN_ERR_UNSUPPORTED;
+    // a complex output always tracks signs: a POSITIVE promise then changes nothing
+    const bool positive = ((flags & HEINSEN_POSITIVE) && !complex_out) || log_in;
+    if ((flags & HEINSEN_LOG_OUTPUT) && !positive && !complex_out) return HEINSEN_ERR_UNSUPPORTED;
     // tile counters are 32-bit: far beyond any array that fits the device, but checked all the same
     if (B * D * n >= ((int64_t)1 << 42)) return HEINSEN_ERR_UNSUPPORTED;
     c.B = B;
@@ -110,7 +115,7 @@ int heinsen_scan(const void *a, const void *b, const void *x0, void *out, int64_
     if (st != HEINSEN_OK) return st;
     const uintptr_t in_align = c.bf16 ? 2 : 4;
     if (reinterpret_cast<uintptr_t>(a) % in_align || reinterpret_cast<uintptr_t>(b) % in_align ||
-        reinterpret_cast<uintptr_t>(x0) % 4 || reinterpret_cast<uintptr_t>(out) % 4)
+        reinterpret_cast<uintptr_t>(x0) % 4 || reinterpret_cast<uintptr_t>(out) % ((flags & HEINSEN_OUT_COMPLEX) ? 8 : 4))
         return HEINSEN_ERR_INVALID_ARG;
     c.a = a;
     c.b = b;

@@ -11,7 +11,7 @@ struct ScanCall {
     const void *a;
     const void *b;
     const float *x0;
-    float *out;
+    float *out;           // float32 per element, or (re, im) pairs when is_signed && log_out
     int64_t B, D, n;      // for the sequence-contiguous path: rows = B*D, row length n
     bool is_signed;       // sign tracking needed (neither POSITIVE nor LOG_INPUTS)
     bool log_in, log_out; // natural-log inputs / output
@@ -48,7 +48,7 @@ const char *bdn_kernel_name(const ScanCall &c);
 static inline int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
 static inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 
-// Expands to a switch over the ten legal (SIGNED, LOG_IN, LOG_OUT, InT) combinations and invokes
+// Expands to a switch over the twelve legal (SIGNED, LOG_IN, LOG_OUT, InT) combinations and invokes
 // F<SIGNED, LOG_IN, LOG_OUT, InT>(__VA_ARGS__).
 #define HS_DISPATCH_MODE(call, F, ...)                                                         \
     do {                                                                                       \
@@ -58,6 +58,7 @@ static inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; 
                 if (c_.log_out) return F<false, true, true, uint16_t>(__VA_ARGS__);            \
                 return F<false, true, false, uint16_t>(__VA_ARGS__);                           \
             }                                                                                  \
+            if (c_.is_signed && c_.log_out) return F<true, false, true, uint16_t>(__VA_ARGS__); \
             if (c_.is_signed) return F<true, false, false, uint16_t>(__VA_ARGS__);             \
             if (c_.log_out) return F<false, false, true, uint16_t>(__VA_ARGS__);               \
             return F<false, false, false, uint16_t>(__VA_ARGS__);                              \
@@ -66,6 +67,7 @@ static inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; 
                 if (c_.log_out) return F<false, true, true, float>(__VA_ARGS__);               \
                 return F<false, true, false, float>(__VA_ARGS__);                              \
             }                                                                                  \
+            if (c_.is_signed && c_.log_out) return F<true, false, true, float>(__VA_ARGS__);    \
             if (c_.is_signed) return F<true, false, false, float>(__VA_ARGS__);                \
             if (c_.log_out) return F<false, false, true, float>(__VA_ARGS__);                  \
             return F<false, false, false, float>(__VA_ARGS__);                                 \

@@ -111,15 +111,20 @@ __device__ __forceinline__ void encode(float v, float &l, uint32_t &s)
 // or, for a log output, log x_k = slae(lx + A_k, M_k) (Eq. (1)).  Two floats are kept per element:
 //   linear output: r0 = A_k, r1 = (+-)2^(M_k) already exponentiated with its sign in the sign bit; the
 //                  sign of the 2^A factor goes to bit k of the lane's sign word `sw`;
-//   log output:    r0 = A_k, r1 = M_k (positive domain, no signs).
+//   log output:    r0 = A_k, r1 = M_k; on a signed domain the signs of the two terms go to bit k of
+//                  `sw` and of `sm`.
 // The first term is formed in the log domain so that a large local product times a small state (or
 // the reverse) does not overflow or flush on the way.
 template <bool SIGNED, bool LOG_OUT>
-__device__ __forceinline__ void stash(const Seg &run, int k, float &r0, float &r1, uint32_t &sw)
+__device__ __forceinline__ void stash(const Seg &run, int k, float &r0, float &r1, uint32_t &sw, uint32_t &sm)
 {
     r0 = run.A;
     if (LOG_OUT) {
         r1 = run.M;
+        if (SIGNED) {
+            sw |= (run.sA >> 31) << k;
+            sm |= (run.sM >> 31) << k;
+        }
     } else {
         const float e = exp2_hw(run.M);
         r1 = SIGNED ? u2f(f2u(e) ^ (run.sM & kSignBit)) : e;
@@ -151,6 +156,19 @@ __device__ __forceinline__ float emit(const State &x, float r0, float r1, uint32
     float e = exp2_hw(x.lx + r0);
     if (SIGNED) e = u2f(f2u(e) ^ ((swx << (31 - k)) & kSignBit));
     return e + r1;
+}
+
+// Log output on a signed domain: the complex logarithm of x_k (Sec. 1, last paragraph), real part
+// log|x_k|, imaginary part pi where x_k < 0 and 0 elsewhere.
+constexpr float kPi = 3.14159265358979323846f;
+__device__ __forceinline__ void emit_clog(const State &x, float r0, float r1, uint32_t swx, uint32_t sm, int k, float &re,
+                                          float &im)
+{
+    float r;
+    uint32_t sr;
+    slae<true>(x.lx + r0, swx << (31 - k), r1, sm << (31 - k), r, sr);
+    re = r * kLn2;
+    im = (sr & kSignBit) ? kPi : 0.0f;
 }
 
 // ---- wave64 cross-lane scan of segment summaries (DPP row shifts + row broadcasts) -----------------

@@ -6,9 +6,8 @@
 //    state at its first step and emits its elements.  No LDS, no barrier, no global scratch.
 //  * tiles: rows longer than that are cut into tiles of NW*64*ITEMS elements, one workgroup per
 //    tile: the same lane and wave scans, wave summaries chained through LDS, tile summaries chained
-//    through global memory.  Tiles of a row are grouped GK at a time; a tile folds the published
-//    summaries of the earlier tiles of its group in a fixed tree (bit-reproducible) onto the state
-//    at the start of the group, which the last tile of the previous group published in float64.
+//    through global memory in a two-level tree (see below); folds happen in a fixed order, so results
+//    are bit-reproducible.
 //
 // What is computed is Sec. 4's expression applied by parts (Sec. 1, footnote on associativity); the
 // arithmetic is in heinsen_math.hpp.
@@ -45,13 +44,13 @@ __device__ __forceinline__ void lane_load(const InT *arow, const InT *brow, int6
     }
 }
 
-// Encodes and scans the lane's elements serially.  On return Av[k], Mv[k] and bit k of sw hold the
-// per-element records (see stash); the summary of all ITEMS steps is returned.
+// Encodes and scans the lane's elements serially.  On return Av[k], Mv[k] and bit k of sw (and of sm)
+// hold the per-element records (see stash); the summary of all ITEMS steps is returned.
 template <bool SIGNED, bool LOG_IN, bool LOG_OUT, int ITEMS>
-__device__ __forceinline__ Seg lane_scan(float (&Av)[ITEMS], float (&Mv)[ITEMS], uint32_t &sw)
+__device__ __forceinline__ Seg lane_scan(float (&Av)[ITEMS], float (&Mv)[ITEMS], uint32_t &sw, uint32_t &sm)
 {
     static_assert(ITEMS <= 32, "sign bits are kept in one word");
-    sw = 0u;
+    sw = sm = 0u;
     Seg run;
 #pragma unroll
     for (int k = 0; k < ITEMS; ++k) {
@@ -67,22 +66,9 @@ __device__ __forceinline__ Seg lane_scan(float (&Av)[ITEMS], float (&Mv)[ITEMS],
             run.A += la;
             if (SIGNED) run.sA ^= sa;
         }
-        stash<SIGNED, LOG_OUT>(run, k, Av[k], Mv[k], sw);
+        stash<SIGNED, LOG_OUT>(run, k, Av[k], Mv[k], sw, sm);
     }
     return run;
-}
-
-// Element-wise fallback: emits the lane's elements given the state at the lane's first step.
-template <bool SIGNED, bool LOG_OUT, int ITEMS>
-__device__ __forceinline__ void lane_emit(float *orow, int64_t start, int64_t n, const State &st,
-                                          const float (&Av)[ITEMS], const float (&Mv)[ITEMS], uint32_t sw)
-{
-    const uint32_t swx = fold_state_sign<SIGNED>(sw, st);
-#pragma unroll
-    for (int k = 0; k < ITEMS; ++k) {
-        const float o = emit<SIGNED, LOG_OUT>(st, Av[k], Mv[k], swx, k);
-        if (start + k < n) orow[start + k] = o;
-    }
 }
 
 // ---- one wave per row -------------------------------------------------------------------------------
@@ -152,6 +138,31 @@ __device__ __forceinline__ void wave_store_blocked(u32x4 *row, int64_t n_vec, u3
     wave_lds_order();
 }
 
+// Lanes (blocked) -> global when a lane owns NV * PARTS consecutive vectors of the row: they are staged
+// NV at a time (round `part` moves vectors part*NV .. part*NV + NV - 1 of every lane), so the region is
+// the same size as for NV vectors and every store instruction still writes whole runs of NV vectors.
+template <int NV, int PARTS>
+__device__ __forceinline__ void wave_store_blocked_part(u32x4 *row, int64_t n_vec, u32x4 *lds, int lane, int part,
+                                                        const u32x4 (&v)[NV])
+{
+#pragma unroll
+    for (int q = 0; q < NV; ++q) lds[lane * (NV + 1) + q] = v[q];
+    wave_lds_order();
+    u32x4 t[NV];
+#pragma unroll
+    for (int j = 0; j < NV; ++j) {
+        const int c = j * 64 + lane;
+        t[j] = lds[c + c / NV];
+    }
+#pragma unroll
+    for (int j = 0; j < NV; ++j) {
+        const int c = j * 64 + lane;
+        const int gi = (c / NV) * (NV * PARTS) + part * NV + c % NV;
+        if (gi < n_vec) __builtin_nontemporal_store(t[j], row + gi);
+    }
+    wave_lds_order();
+}
+
 template <typename InT, int NVI, int ITEMS>
 __device__ __forceinline__ void unpack_inputs(const u32x4 (&v)[NVI], float (&x)[ITEMS])
 {
@@ -172,6 +183,57 @@ __device__ __forceinline__ void unpack_inputs(const u32x4 (&v)[NVI], float (&x)[
 }
 
 
+// Element-wise fallback: emits the lane's elements given the state at the lane's first step.
+template <bool SIGNED, bool LOG_OUT, int ITEMS>
+__device__ __forceinline__ void lane_emit(float *orow, int64_t start, int64_t n, const State &st,
+                                          const float (&Av)[ITEMS], const float (&Mv)[ITEMS], uint32_t sw, uint32_t sm)
+{
+    const uint32_t swx = fold_state_sign<SIGNED>(sw, st);
+#pragma unroll
+    for (int k = 0; k < ITEMS; ++k) {
+        if constexpr (SIGNED && LOG_OUT) {
+            float re, im;
+            emit_clog(st, Av[k], Mv[k], swx, sm, k, re, im);
+            if (start + k < n) {
+                orow[2 * (start + k)] = re;
+                orow[2 * (start + k) + 1] = im;
+            }
+        } else {
+            const float o = emit<SIGNED, LOG_OUT>(st, Av[k], Mv[k], swx, k);
+            if (start + k < n) orow[start + k] = o;
+        }
+    }
+}
+
+// Complex output (log output on a signed domain), vector path: emits the lane's elements and writes them,
+// coalesced, through the wave's LDS region.  `orow` points at the wave's first output element, n_elems
+// elements of the row are left from there (a multiple of four).  The output has twice the bytes of a real
+// one and goes through the region in two rounds.
+template <int ITEMS>
+__device__ __forceinline__ void wave_emit_clog_blocked(float *orow, int64_t n_elems, u32x4 *lds, int lane, const State &st,
+                                                       const float (&Av)[ITEMS], const float (&Mv)[ITEMS], uint32_t sw,
+                                                       uint32_t sm)
+{
+    constexpr int NVO = ITEMS / 4;
+    const uint32_t swx = fold_state_sign<true>(sw, st);
+    n_elems = n_elems < 0 ? 0 : n_elems;
+#pragma unroll
+    for (int part = 0; part < 2; ++part) {
+        u32x4 vo[NVO];
+#pragma unroll
+        for (int q = 0; q < NVO; ++q)
+#pragma unroll
+            for (int i = 0; i < 2; ++i) {
+                const int k = part * (ITEMS / 2) + q * 2 + i;
+                float re, im;
+                emit_clog(st, Av[k], Mv[k], swx, sm, k, re, im);
+                vo[q][2 * i] = f2u(re);
+                vo[q][2 * i + 1] = f2u(im);
+            }
+        wave_store_blocked_part<NVO, 2>(reinterpret_cast<u32x4 *>(orow), n_elems / 2, lds, lane, part, vo);
+    }
+}
+
 template <bool SIGNED, bool LOG_IN, bool LOG_OUT, typename InT, int ITEMS, bool VECIO>
 __global__ __launch_bounds__(256, VECIO ? 4 : 1) void heinsen_scan_rows_wave(RowsParams p)
 {
@@ -183,11 +245,12 @@ __global__ __launch_bounds__(256, VECIO ? 4 : 1) void heinsen_scan_rows_wave(Row
     if (row >= p.rows) return; // whole wave leaves together
     const InT *arow = reinterpret_cast<const InT *>(p.a) + row * p.n;
     const InT *brow = reinterpret_cast<const InT *>(p.b) + row * p.n;
-    float *orow = p.out + row * p.n;
+    constexpr int OW = (SIGNED && LOG_OUT) ? 2 : 1; // floats per output element
+    float *orow = p.out + OW * row * p.n;
     const int64_t start = (int64_t)lane * ITEMS;
 
     float Av[ITEMS], Mv[ITEMS];
-    uint32_t sw;
+    uint32_t sw, sm;
     if (VECIO) {
         constexpr int VL = 16 / (int)sizeof(InT);
         constexpr int NVI = ITEMS / VL;
@@ -205,13 +268,15 @@ __global__ __launch_bounds__(256, VECIO ? 4 : 1) void heinsen_scan_rows_wave(Row
     } else {
         lane_load<LOG_IN, InT, ITEMS>(arow, brow, start, p.n, Av, Mv);
     }
-    Seg mine = lane_scan<SIGNED, LOG_IN, LOG_OUT, ITEMS>(Av, Mv, sw);
+    Seg mine = lane_scan<SIGNED, LOG_IN, LOG_OUT, ITEMS>(Av, Mv, sw, sm);
     Seg excl = wave_shift_up<SIGNED>(wave_inclusive_scan<SIGNED>(mine));
 
     State st;
     encode<SIGNED, LOG_IN>(p.x0[p.x0_stride ? row : 0], st.lx, st.s);
     st = seg_apply<SIGNED>(st, excl);
-    if (VECIO) {
+    if constexpr (VECIO && SIGNED && LOG_OUT) {
+        wave_emit_clog_blocked<ITEMS>(orow, p.n, stage[w], lane, st, Av, Mv, sw, sm);
+    } else if (VECIO) {
         constexpr int NVO = ITEMS / 4;
         const uint32_t swx = fold_state_sign<SIGNED>(sw, st);
         u32x4 vo[NVO];
@@ -222,7 +287,7 @@ __global__ __launch_bounds__(256, VECIO ? 4 : 1) void heinsen_scan_rows_wave(Row
                 vo[q][i] = f2u(emit<SIGNED, LOG_OUT>(st, Av[q * 4 + i], Mv[q * 4 + i], swx, q * 4 + i));
         wave_store_blocked<NVO>(reinterpret_cast<u32x4 *>(orow), p.n / 4, stage[w], lane, vo);
     } else {
-        lane_emit<SIGNED, LOG_OUT, ITEMS>(orow, start, p.n, st, Av, Mv, sw);
+        lane_emit<SIGNED, LOG_OUT, ITEMS>(orow, start, p.n, st, Av, Mv, sw, sm);
     }
 }
 
@@ -363,7 +428,7 @@ __global__ __launch_bounds__(kTileWaves * 64) void heinsen_scan_tiles(TileParams
     __shared__ u32x4 stage[VECIO ? NW : 1][VECIO ? 64 * (ITEMS / 4 + 1) - 1 : 1];
     const int64_t wstart = (int64_t)c * kTile + (int64_t)w * (64 * ITEMS); // first element of this wave
     float Av[ITEMS], Mv[ITEMS];
-    uint32_t sw;
+    uint32_t sw, sm;
     if (VECIO) {
         constexpr int VL = 16 / (int)sizeof(InT);
         constexpr int NVI = ITEMS / VL;
@@ -380,7 +445,7 @@ __global__ __launch_bounds__(kTileWaves * 64) void heinsen_scan_tiles(TileParams
     } else {
         lane_load<LOG_IN, InT, ITEMS>(arow, brow, start, p.n, Av, Mv);
     }
-    Seg mine = lane_scan<SIGNED, LOG_IN, LOG_OUT, ITEMS>(Av, Mv, sw);
+    Seg mine = lane_scan<SIGNED, LOG_IN, LOG_OUT, ITEMS>(Av, Mv, sw, sm);
     Seg incl = wave_inclusive_scan<SIGNED>(mine);
     Seg lane_excl = wave_shift_up<SIGNED>(incl);
     HS_STAMP(1);
@@ -472,7 +537,11 @@ __global__ __launch_bounds__(kTileWaves * 64) void heinsen_scan_tiles(TileParams
     st.lx = lds_startL;
     st.s = lds_startS;
     st = seg_apply<SIGNED>(st, seg_combine<SIGNED>(wave_excl, lane_excl));
-    if (VECIO) {
+    constexpr int OW = (SIGNED && LOG_OUT) ? 2 : 1; // floats per output element
+    float *orow = p.out + OW * row * p.n;
+    if constexpr (VECIO && SIGNED && LOG_OUT) {
+        wave_emit_clog_blocked<ITEMS>(orow + OW * wstart, p.n - wstart, stage[w], lane, st, Av, Mv, sw, sm);
+    } else if (VECIO) {
         constexpr int NVO = ITEMS / 4;
         const uint32_t swx = fold_state_sign<SIGNED>(sw, st);
         u32x4 vo[NVO];
@@ -483,9 +552,9 @@ __global__ __launch_bounds__(kTileWaves * 64) void heinsen_scan_tiles(TileParams
                 vo[qv][i] = f2u(emit<SIGNED, LOG_OUT>(st, Av[qv * 4 + i], Mv[qv * 4 + i], swx, qv * 4 + i));
         int64_t n_vec = (p.n - wstart) / 4;
         n_vec = n_vec < 0 ? 0 : n_vec;
-        wave_store_blocked<NVO>(reinterpret_cast<u32x4 *>(p.out + row * p.n + wstart), n_vec, stage[w], lane, vo);
+        wave_store_blocked<NVO>(reinterpret_cast<u32x4 *>(orow + wstart), n_vec, stage[w], lane, vo);
     } else {
-        lane_emit<SIGNED, LOG_OUT, ITEMS>(p.out + row * p.n, start, p.n, st, Av, Mv, sw);
+        lane_emit<SIGNED, LOG_OUT, ITEMS>(orow, start, p.n, st, Av, Mv, sw, sm);
     }
     HS_STAMP(6);
     HS_STAMP(7);

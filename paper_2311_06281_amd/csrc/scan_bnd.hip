@@ -22,7 +22,7 @@ struct BndParams {
     const void *a;
     const void *b;
     const float *x0;
-    float *out;
+    float *out;       // float32 per element; (re, im) float32 pairs for a log output on a signed domain
     int64_t D, n;
     int x0_stride;    // 0: one x0 for all, 1: x0[b*D + d]
     int stream_out;   // 1: the output does not fit the last-level cache, write it non-temporally
@@ -210,10 +210,10 @@ __global__ __launch_bounds__(NW * 64, MINW) void heinsen_scan_bnd(BndParams p)
     if (w == 0) have_records = records_in(); // first look: answered while the tile's loads were in flight
 
     // ---- encode + serial scan in each lane; Av/Mv become the per-element records (see stash) --------
-    uint32_t sw[VEC];
+    uint32_t sw[VEC], sm[VEC];
     Seg run[VEC];
 #pragma unroll
-    for (int v = 0; v < VEC; ++v) sw[v] = 0u;
+    for (int v = 0; v < VEC; ++v) sw[v] = sm[v] = 0u;
 #pragma unroll
     for (int k = 0; k < T; ++k) {
 #pragma unroll
@@ -230,7 +230,7 @@ __global__ __launch_bounds__(NW * 64, MINW) void heinsen_scan_bnd(BndParams p)
                 run[v].A += la;
                 if (SIGNED) run[v].sA ^= sa;
             }
-            stash<SIGNED, LOG_OUT>(run[v], k, Av[k][v], Mv[k][v], sw[v]);
+            stash<SIGNED, LOG_OUT>(run[v], k, Av[k][v], Mv[k][v], sw[v], sm[v]);
         }
         if (SB) __builtin_amdgcn_sched_barrier(0);
     }
@@ -335,17 +335,26 @@ __global__ __launch_bounds__(NW * 64, MINW) void heinsen_scan_bnd(BndParams p)
         st[v].s = lds_startS[loff + v];
         if (w > 0) st[v] = seg_apply<SIGNED>(st[v], pre[v]);
     }
-    float *op = p.out + ubase;
+    constexpr int OW = (SIGNED && LOG_OUT) ? 2 : 1; // floats per output element
+    float *op = p.out + OW * ubase;
     const bool full = chan_ok && t0 + T <= p.n;
     uint32_t swx[VEC];
 #pragma unroll
     for (int v = 0; v < VEC; ++v) swx[v] = fold_state_sign<SIGNED>(sw[v], st[v]);
 #pragma unroll
     for (int k = 0; k < T; ++k) {
-        float o[VEC];
+        if constexpr (SIGNED && LOG_OUT) {
+            // complex output: (re, im) pairs, two floats per element
+            float o[2 * VEC];
 #pragma unroll
-        for (int v = 0; v < VEC; ++v) o[v] = emit<SIGNED, LOG_OUT>(st[v], Av[k][v], Mv[k][v], swx[v], k);
-        if (full || (chan_ok && t0 + k < p.n)) store_vec(op + (int64_t)k * p.D + loff, o, p.stream_out != 0);
+            for (int v = 0; v < VEC; ++v) emit_clog(st[v], Av[k][v], Mv[k][v], swx[v], sm[v], k, o[2 * v], o[2 * v + 1]);
+            if (full || (chan_ok && t0 + k < p.n)) store_vec(op + 2 * ((int64_t)k * p.D + loff), o, p.stream_out != 0);
+        } else {
+            float o[VEC];
+#pragma unroll
+            for (int v = 0; v < VEC; ++v) o[v] = emit<SIGNED, LOG_OUT>(st[v], Av[k][v], Mv[k][v], swx[v], k);
+            if (full || (chan_ok && t0 + k < p.n)) store_vec(op + (int64_t)k * p.D + loff, o, p.stream_out != 0);
+        }
         if (SB) __builtin_amdgcn_sched_barrier(0);
     }
     HS_STAMP(7);
@@ -394,7 +403,8 @@ BndPlan make_plan(const ScanCall &c)
     pl.T = 32;
     pl.NW = 8;
     pl.G = 4;
-    if (c.bf16 && c.D % 2 == 0 && aligned(c.a, 2 * in_sz) && aligned(c.b, 2 * in_sz) && aligned(c.out, 8)) {
+    if (c.bf16 && c.D % 2 == 0 && aligned(c.a, 2 * in_sz) && aligned(c.b, 2 * in_sz) &&
+        aligned(c.out, (c.is_signed && c.log_out) ? 16 : 8)) {
         pl.vec = 2;
         pl.T = 16;
         pl.NW = 8;
@@ -436,7 +446,7 @@ hipError_t launch_mode(const ScanCall &c, const BndPlan &pl, rec_t *records, Lau
     p.D = c.D;
     p.n = c.n;
     p.x0_stride = c.x0_scalar ? 0 : 1;
-    p.stream_out = (c.B * c.D * c.n * 4 > kLastLevelCacheBytes) ? 1 : 0;
+    p.stream_out = (c.B * c.D * c.n * ((SIGNED && LOG_OUT) ? 8 : 4) > kLastLevelCacheBytes) ? 1 : 0;
     p.cols_per_b = pl.cols_per_b;
     p.ncols = pl.ncols;
     p.nchunks = pl.nchunks;

@@ -58,7 +58,11 @@ P = 4096  # a non-null, aligned fake address: validation must fail before it is 
     ((P + 2, P, P, P, 1, 1, 8, 0, 0), hb.HEINSEN_ERR_INVALID_ARG),      # misaligned float32 input
     ((P + 1, P, P, P, 1, 1, 8, 0, hb.HEINSEN_IN_BF16), hb.HEINSEN_ERR_INVALID_ARG),  # misaligned bf16 input
     ((P, P, P, P + 2, 1, 1, 8, 0, 0), hb.HEINSEN_ERR_INVALID_ARG),      # misaligned out
-    ((P, P, P, P, 1, 1, 8, 0, hb.HEINSEN_LOG_OUTPUT), hb.HEINSEN_ERR_UNSUPPORTED),  # log of a signed result
+    ((P, P, P, P, 1, 1, 8, 0, hb.HEINSEN_LOG_OUTPUT), hb.HEINSEN_ERR_UNSUPPORTED),  # real log of a signed result
+    ((P, P, P, P, 1, 1, 8, 0, hb.HEINSEN_OUT_COMPLEX), hb.HEINSEN_ERR_INVALID_ARG),  # complex output of a linear result
+    ((P, P, P, P, 1, 1, 8, 0, hb.HEINSEN_OUT_COMPLEX | hb.HEINSEN_LOG_OUTPUT | hb.HEINSEN_LOG_INPUTS),
+     hb.HEINSEN_ERR_UNSUPPORTED),                                       # complex output of log-domain inputs
+    ((P, P, P, P + 4, 1, 1, 8, 0, hb.HEINSEN_OUT_COMPLEX | hb.HEINSEN_LOG_OUTPUT), hb.HEINSEN_ERR_INVALID_ARG),  # misaligned complex out
 ])
 def test_bad_arguments_are_rejected_on_the_host(args, expect):
     assert hb.heinsen_scan_status(*args) == expect

@@ -28,7 +28,7 @@ def _inputs(rng, shape, layout, mode):
     """Stored inputs (float32 arrays holding exactly what the GPU reads) for one mode."""
     B = shape[0]
     D = shape[2] if layout == "BND" else shape[1]
-    if mode == "signed":
+    if mode in ("signed", "signed_clog"):
         a = rng.uniform(-1.1, 1.1, shape)
         b = rng.normal(0, 1, shape)
         x0 = rng.normal(0, 1, B * D)
@@ -49,6 +49,7 @@ MODES = {
     "positive_logout": ("POSITIVE", "LOG_OUTPUT"),
     "log": ("LOG_INPUTS",),
     "log_logout": ("LOG_INPUTS", "LOG_OUTPUT"),
+    "signed_clog": ("LOG_OUTPUT", "OUT_COMPLEX"),
 }
 SHAPES = {
     "BDN": [(2, 3, 1), (1, 5, 17), (2, 3, 520), (1, 2, 2048), (1, 3, 2056), (1, 1, 16384 * 3 + 8), (3, 2, 16384 + 1)],
@@ -77,15 +78,17 @@ def _run(gpu, a, b, x0, layout, flag_names, bf16, offset_elems=0):
     keep_a, a_t = dev(a, bf16)
     keep_b, b_t = dev(b, bf16)
     x_t = torch.from_numpy(x0).cuda()
-    keep_o = torch.full((a.size + offset_elems + 8,), float("nan"), dtype=torch.float32, device="cuda")
-    o_t = keep_o[offset_elems:]
+    ow = 2 if "OUT_COMPLEX" in flag_names else 1  # floats per output element
+    keep_o = torch.full((ow * (a.size + offset_elems) + 8,), float("nan"), dtype=torch.float32, device="cuda")
+    o_t = keep_o[ow * offset_elems:]
     flags = hb.flags_from_names(flag_names) | (hb.HEINSEN_IN_BF16 if bf16 else 0)
     hb.heinsen_scan(a_t, b_t, x_t, o_t, B, D, n, hb.LAYOUTS[layout], flags, torch.cuda.current_stream())
     torch.cuda.synchronize()
     res = keep_o.cpu().numpy()
     # nothing outside the output range was touched
-    assert np.isnan(res[:offset_elems]).all() and np.isnan(res[offset_elems + a.size:]).all()
-    return res[offset_elems:offset_elems + a.size].reshape(a.shape)
+    assert np.isnan(res[:ow * offset_elems]).all() and np.isnan(res[ow * (offset_elems + a.size):]).all()
+    res = res[ow * offset_elems:ow * (offset_elems + a.size)]
+    return res.reshape(a.shape + (2,)) if ow == 2 else res.reshape(a.shape)
 
 
 def _check(got, a, b, x0, layout, mode):
@@ -94,11 +97,22 @@ def _check(got, a, b, x0, layout, mode):
         ref = np.exp(oracle.sequential_log(a, b, x0, layout=lay))
     else:
         ref = oracle.sequential(a, b, x0, layout=lay)
-    val = np.exp(got.astype(np.float64)) if mode.endswith("logout") else got.astype(np.float64)
+    if mode == "signed_clog":
+        # complex logarithm: the imaginary part is exactly 0 or float32(pi); back in the linear domain
+        # the value is held to the signed bound
+        re, im = got[..., 0].astype(np.float64), got[..., 1]
+        assert np.all((im == 0) | (im == np.float32(np.pi)))
+        val = np.exp(re) * np.where(im == 0, 1.0, -1.0)
+    else:
+        val = np.exp(got.astype(np.float64)) if mode.endswith("logout") else got.astype(np.float64)
     err = np.abs(val - ref)
-    if mode == "signed":
+    if mode in ("signed", "signed_clog"):
+        # running scale max_{0<=s<=t} |x_s|: it starts at |x_0|, which is a member of the sequence (a first
+        # step that cancels, x_1 = a_1 x_0 + b_1 ~ 0, has no other scale to be measured against)
         axis = 1 if layout == "BND" else 2
-        bound = SIGNED_RTOL * np.maximum.accumulate(np.abs(ref), axis=axis)
+        shp = (a.shape[0], 1, a.shape[2]) if layout == "BND" else (a.shape[0], a.shape[1], 1)
+        scale = np.maximum(np.maximum.accumulate(np.abs(ref), axis=axis), np.abs(x0.astype(np.float64)).reshape(shp))
+        bound = SIGNED_RTOL * scale
     else:
         bound = POS_RTOL * np.abs(ref) + POS_ATOL
     assert np.all(err <= bound), f"worst error/bound {np.max(err / (bound + 1e-300)):.3g}"
@@ -132,6 +146,18 @@ def test_pointers_that_are_only_element_aligned(gpu, layout, shape, bf16, offset
         b = workloads.bf16_bits_to_f32(workloads.f32_to_bf16_bits(b)).reshape(shape)
     got = _run(gpu, a, b, x0, layout, (), bf16, offset_elems=offset)
     _check(got, a, b, x0, layout, "signed")
+
+
+@pytest.mark.parametrize("layout,shape", [("BDN", (2, 3, 2048)), ("BDN", (1, 2, 16384 * 2 + 16)), ("BND", (1, 300, 128)), ("BND", (2, 64, 66))])
+@pytest.mark.parametrize("bf16", [False, True])
+def test_complex_output_with_element_aligned_pointers(gpu, layout, shape, bf16):
+    rng = np.random.default_rng(7)
+    a, b, x0 = _inputs(rng, shape, layout, "signed_clog")
+    if bf16:
+        a = workloads.bf16_bits_to_f32(workloads.f32_to_bf16_bits(a)).reshape(shape)
+        b = workloads.bf16_bits_to_f32(workloads.f32_to_bf16_bits(b)).reshape(shape)
+    got = _run(gpu, a, b, x0, layout, MODES["signed_clog"], bf16, offset_elems=1)
+    _check(got, a, b, x0, layout, "signed_clog")
 
 
 def test_interleaved_shapes_on_one_stream_share_scratch_safely(gpu):

@@ -160,6 +160,35 @@ def test_overflow_goes_to_infinity_where_float32_ends(gpu):
     assert np.isinf(got[ref > 3.5e38]).all() and (got[ref > 3.5e38] > 0).all()
 
 
+@pytest.mark.parametrize("layout,shape", [("BDN", (1, 2, 1500)), ("BDN", (1, 1, 40000)), ("BND", (1, 1200, 66))])
+def test_complex_log_output_stays_finite_where_the_value_leaves_float32(gpu, layout, shape):
+    """|x_t| grows like 3^t, far past float32 and float64: its complex logarithm is what can be stored."""
+    torch, hb = gpu
+    rng = np.random.default_rng(11)
+    a = np.where(rng.random(shape) < 0.5, -3.0, 3.0).astype(np.float32)
+    b = rng.normal(0, 0.3, shape).astype(np.float32)
+    if layout == "BND":
+        B, n, D = shape
+    else:
+        B, D, n = shape
+    x0 = np.where(rng.random(B * D) < 0.5, -1.0, 1.0).astype(np.float32)
+    a_t, b_t, x_t = (torch.from_numpy(v).cuda() for v in (a, b, x0))
+    o_t = torch.full(shape + (2,), float("nan"), dtype=torch.float32, device="cuda")
+    hb.heinsen_scan(a_t, b_t, x_t, o_t, B, D, n, hb.LAYOUTS[layout], hb.HEINSEN_LOG_OUTPUT | hb.HEINSEN_OUT_COMPLEX,
+                    torch.cuda.current_stream())
+    torch.cuda.synchronize()
+    got = o_t.cpu().numpy()
+    assert np.isfinite(got[..., 0]).all()
+    assert np.all((got[..., 1] == 0) | (got[..., 1] == np.float32(np.pi)))
+    for bi in range(B):
+        for d in range(min(D, 6)):
+            sel = (bi, slice(None), d) if layout == "BND" else (bi, d, slice(None))
+            ref = oracle.seq_clog_scaled(a[sel], b[sel], x0[bi * D + d])
+            re, im = got[sel][:, 0].astype(np.float64), got[sel][:, 1]
+            assert np.all(np.abs(re - ref.real) <= 1e-5 * np.abs(ref.real) + 1e-3), float(np.max(np.abs(re - ref.real)))
+            np.testing.assert_array_equal(im != 0, ref.imag != 0)
+
+
 def test_large_local_product_times_small_state_does_not_overflow_on_the_way(gpu):
     # x grows from 1e-30 by 1e5 per step: every x_t fits float32 although prod(a) alone would not
     n = 12

@@ -267,6 +267,32 @@ def test_complex_log_agrees_with_closed_form_in_the_complex_domain(idx):
         np.testing.assert_allclose(dphi, np.rint(dphi), rtol=0, atol=1e-6)
 
 
+def test_scaled_complex_log_matches_plain_one_in_range_and_closed_form_beyond():
+    rng = np.random.default_rng(3)
+    n = 200
+    a = rng.uniform(-1.2, 1.2, n).astype(np.float32)
+    b = rng.normal(0, 1, n).astype(np.float32)
+    z = oracle.seq_clog_scaled(a, b, float(np.float32(-0.7)))
+    ref = oracle.sequential_clog(a.reshape(1, 1, n), b.reshape(1, 1, n), np.array([-0.7], np.float32))[0, 0]
+    x = oracle.seq_f64(a.astype(np.float64), b.astype(np.float64), float(np.float32(-0.7)))
+    # cancellation (small |x_t| from large terms) amplifies rounding in the logarithm: compare the values
+    runmax = np.maximum.accumulate(np.abs(x))
+    assert np.all(np.abs(np.exp(z.real) * np.cos(z.imag) - x) <= 1e-13 * runmax)
+    big = np.abs(x) > 1e-3 * runmax
+    np.testing.assert_allclose(z.real[big], ref.real[big], rtol=0, atol=1e-9)
+    np.testing.assert_array_equal(z.imag[big], ref.imag[big])
+    # beyond float64: b = 0, a = -1e200: log|x_t| = t log 1e200, sign alternates
+    m = 12
+    z = oracle.seq_clog_scaled(np.full(m, -1e200), np.zeros(m), 1.0)
+    t = np.arange(1, m + 1)
+    np.testing.assert_allclose(z.real, t * np.log(1e200), rtol=1e-14)
+    np.testing.assert_array_equal(z.imag != 0, t % 2 == 1)
+    # zero state restarts from b
+    z = oracle.seq_clog_scaled(np.array([0.0, 2.0]), np.array([-3.0, 0.0]), 5.0)
+    np.testing.assert_allclose(z.real, [np.log(3.0), np.log(6.0)], rtol=1e-15)
+    np.testing.assert_array_equal(z.imag, [np.pi, np.pi])
+
+
 def test_log_domain_definition_matches_linear_definition():
     cfg = workloads.CONFIGS[4].scaled(B=2, D=4, n=256)
     batch = workloads.generate(cfg)
