@@ -403,8 +403,12 @@ BndPlan make_plan(const ScanCall &c)
     pl.T = 32;
     pl.NW = 8;
     pl.G = 4;
-    if (c.bf16 && c.D % 2 == 0 && aligned(c.a, 2 * in_sz) && aligned(c.b, 2 * in_sz) &&
-        aligned(c.out, (c.is_signed && c.log_out) ? 16 : 8)) {
+    if (c.is_signed && c.log_out) {
+        // complex output: the signed log-domain emit needs more registers per element; 16 steps per wave
+        // and 16 waves keep the tile the same and the kernel free of spills
+        pl.T = 16;
+        pl.NW = 16;
+    } else if (c.bf16 && c.D % 2 == 0 && aligned(c.a, 2 * in_sz) && aligned(c.b, 2 * in_sz) && aligned(c.out, 8)) {
         pl.vec = 2;
         pl.T = 16;
         pl.NW = 8;
@@ -473,10 +477,14 @@ hipError_t launch_mode(const ScanCall &c, const BndPlan &pl, rec_t *records, Lau
 #undef X
     }
 #endif
-    if (pl.vec == 2)
-        hipLaunchKernelGGL((heinsen_scan_bnd<SIGNED, LOG_IN, LOG_OUT, InT, 2, 16, 8, 4, 4, true>), grid, block, 0, c.stream, p);
-    else
-        hipLaunchKernelGGL((heinsen_scan_bnd<SIGNED, LOG_IN, LOG_OUT, InT, 1, 32, 8, 4, 4, true>), grid, block, 0, c.stream, p);
+    if constexpr (SIGNED && LOG_OUT) {
+        hipLaunchKernelGGL((heinsen_scan_bnd<SIGNED, LOG_IN, LOG_OUT, InT, 1, 16, 16, 4, 4, true>), grid, block, 0, c.stream, p);
+    } else {
+        if (pl.vec == 2)
+            hipLaunchKernelGGL((heinsen_scan_bnd<SIGNED, LOG_IN, LOG_OUT, InT, 2, 16, 8, 4, 4, true>), grid, block, 0, c.stream, p);
+        else
+            hipLaunchKernelGGL((heinsen_scan_bnd<SIGNED, LOG_IN, LOG_OUT, InT, 1, 32, 8, 4, 4, true>), grid, block, 0, c.stream, p);
+    }
     return hipGetLastError();
 }
 
