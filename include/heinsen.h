@@ -43,17 +43,25 @@ enum {
     HEINSEN_POSITIVE   = 1u << 3, /* caller promises a_t > 0, b_t >= 0, x_0 >= 0: sign tracking skipped.
                                      With a negative input the result is unspecified but memory-safe.   */
     HEINSEN_X0_SCALAR  = 1u << 4, /* x0 points to ONE float32 that is broadcast to all B*D sequences.    */
-    HEINSEN_OUT_COMPLEX = 1u << 5 /* with LOG_OUTPUT on signed data: out holds B*D*n complex64 values
+    HEINSEN_OUT_COMPLEX = 1u << 5, /* with LOG_OUTPUT on signed data: out holds B*D*n complex64 values
                                      (re, im interleaved), the complex logarithm of x_t (Sec. 1, last
                                      paragraph): re = log|x_t|, im = pi where x_t < 0, else 0; x_t = 0
                                      gives re = -inf.  Signs are always tracked (POSITIVE is ignored).
                                      Not available with LOG_INPUTS.                                     */
+    HEINSEN_LINEAR     = 1u << 6  /* comparison path: the same single-pass scan with the plain operator
+                                     (a1, b1) o (a2, b2) = (a1 a2, a2 b1 + b2) of the general formulation
+                                     the paper compares itself with (Sec. 2), in float32, without any
+                                     logarithm.  Partial products of a_t over up to a tile group of steps
+                                     are formed, so they overflow or flush where the log-space form does
+                                     not.  Excludes LOG_INPUTS, LOG_OUTPUT, OUT_COMPLEX; POSITIVE is
+                                     ignored.                                                            */
 };
 
 typedef enum {
     HEINSEN_OK = 0,
     HEINSEN_ERR_INVALID_ARG = 1, /* null pointer, non-positive size, size overflow, misaligned pointer,
-                                    unknown layout or flag bit                                           */
+                                    unknown layout or flag bit, contradictory flags (OUT_COMPLEX without
+                                    LOG_OUTPUT, LINEAR with a log-domain flag)                           */
     HEINSEN_ERR_UNSUPPORTED = 2, /* a legal but unimplemented combination: LOG_OUTPUT on a signed domain
                                     without OUT_COMPLEX, OUT_COMPLEX with LOG_INPUTS, a call that needs
                                     scratch while its stream is being captured                         */

@@ -22,8 +22,10 @@ HEINSEN_IN_BF16 = 1 << 2
 HEINSEN_POSITIVE = 1 << 3
 HEINSEN_X0_SCALAR = 1 << 4
 HEINSEN_OUT_COMPLEX = 1 << 5
+HEINSEN_LINEAR = 1 << 6
 FLAGS = {"LOG_INPUTS": HEINSEN_LOG_INPUTS, "LOG_OUTPUT": HEINSEN_LOG_OUTPUT, "IN_BF16": HEINSEN_IN_BF16,
-         "POSITIVE": HEINSEN_POSITIVE, "X0_SCALAR": HEINSEN_X0_SCALAR, "OUT_COMPLEX": HEINSEN_OUT_COMPLEX}
+         "POSITIVE": HEINSEN_POSITIVE, "X0_SCALAR": HEINSEN_X0_SCALAR, "OUT_COMPLEX": HEINSEN_OUT_COMPLEX,
+         "LINEAR": HEINSEN_LINEAR}
 
 HEINSEN_OK = 0
 HEINSEN_ERR_INVALID_ARG = 1

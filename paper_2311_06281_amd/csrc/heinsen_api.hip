@@ -12,7 +12,7 @@ namespace {
 
 constexpr uint32_t kAllFlags =
     HEINSEN_LOG_INPUTS | HEINSEN_LOG_OUTPUT | HEINSEN_IN_BF16 | HEINSEN_POSITIVE | HEINSEN_X0_SCALAR |
-    HEINSEN_OUT_COMPLEX;
+    HEINSEN_OUT_COMPLEX | HEINSEN_LINEAR;
 
 thread_local int t_last_hip_error = 0;
 
@@ -45,6 +45,8 @@ int describe(int64_t B, int64_t D, int64_t n, int layout, uint32_t flags, hs::Sc
     const int64_t lim = (int64_t)1 << 62;
     if (B > lim / D || B * D > lim / n || B * D * n >= lim) return HEINSEN_ERR_INVALID_ARG;
     const bool log_in = flags & HEINSEN_LOG_INPUTS;
+    const bool linear = flags & HEINSEN_LINEAR;
+    if (linear && (flags & (HEINSEN_LOG_INPUTS | HEINSEN_LOG_OUTPUT | HEINSEN_OUT_COMPLEX))) return HEINSEN_ERR_INVALID_ARG;
     const bool complex_out = flags & HEINSEN_OUT_COMPLEX;
     if (complex_out && !(flags & HEINSEN_LOG_OUTPUT)) return HEINSEN_ERR_INVALID_ARG;
     if (complex_out && log_in) return HEINSEN_ERR_UNSUPPORTED;
@@ -56,7 +58,8 @@ int describe(int64_t B, int64_t D, int64_t n, int layout, uint32_t flags, hs::Sc
     c.B = B;
     c.D = D;
     c.n = n;
-    c.is_signed = !positive;
+    c.is_signed = !positive && !linear;
+    c.linear = linear;
     c.log_in = log_in;
     c.log_out = flags & HEINSEN_LOG_OUTPUT;
     c.bf16 = flags & HEINSEN_IN_BF16;

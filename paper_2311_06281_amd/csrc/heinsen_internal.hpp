@@ -15,6 +15,7 @@ struct ScanCall {
     int64_t B, D, n;      // for the sequence-contiguous path: rows = B*D, row length n
     bool is_signed;       // sign tracking needed (neither POSITIVE nor LOG_INPUTS)
     bool log_in, log_out; // natural-log inputs / output
+    bool linear;          // linear-domain comparison path (no logarithms anywhere)
     bool bf16;            // a, b stored as bfloat16
     bool x0_scalar;       // one x0 for all sequences
     hipStream_t stream;
@@ -48,12 +49,13 @@ const char *bdn_kernel_name(const ScanCall &c);
 static inline int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
 static inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 
-// Expands to a switch over the twelve legal (SIGNED, LOG_IN, LOG_OUT, InT) combinations and invokes
-// F<SIGNED, LOG_IN, LOG_OUT, InT>(__VA_ARGS__).
+// Expands to a switch over the fourteen legal (DOM, LOG_IN, LOG_OUT, InT) combinations and invokes
+// F<DOM, LOG_IN, LOG_OUT, InT>(__VA_ARGS__); DOM is 0 (positive), 1 (signed) or 2 (linear), see heinsen_math.hpp.
 #define HS_DISPATCH_MODE(call, F, ...)                                                         \
     do {                                                                                       \
         const ::hs::ScanCall &c_ = (call);                                                     \
         if (c_.bf16) {                                                                         \
+            if (c_.linear) return F<2, false, false, uint16_t>(__VA_ARGS__);                   \
             if (c_.log_in) {                                                                   \
                 if (c_.log_out) return F<false, true, true, uint16_t>(__VA_ARGS__);            \
                 return F<false, true, false, uint16_t>(__VA_ARGS__);                           \
@@ -63,6 +65,7 @@ static inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; 
             if (c_.log_out) return F<false, false, true, uint16_t>(__VA_ARGS__);               \
             return F<false, false, false, uint16_t>(__VA_ARGS__);                              \
         } else {                                                                               \
+            if (c_.linear) return F<2, false, false, float>(__VA_ARGS__);                      \
             if (c_.log_in) {                                                                   \
                 if (c_.log_out) return F<false, true, true, float>(__VA_ARGS__);               \
                 return F<false, true, false, float>(__VA_ARGS__);                              \

@@ -21,6 +21,15 @@ namespace hs {
 // Sign words: bit 31 is the sign (1 = negative); the other 31 bits are undefined and every consumer
 // either ignores them or masks them.  This lets the raw bits of an input float serve as its sign word.
 
+// Domain of the scan, the first template argument of everything below.  A bool converts to the first two
+// (false: positive, true: signed), which is how most callers name them.
+//   kPositive, kSigned: the paper's log-space form (Sec. 1, Sec. 4); A = sum of log2|a|, M = log2 of the
+//                       segment's zero-input response, signs tracked or not;
+//   kLinear:            the same scan with the plain operator (a1, b1) o (a2, b2) = (a1 a2, a2 b1 + b2) of the
+//                       general formulation the paper compares itself with (Sec. 2): A = product of a,
+//                       M = zero-input response, no logarithms.  A comparison path.
+constexpr int kPositive = 0, kSigned = 1, kLinear = 2;
+
 constexpr float kLog2e = 1.44269504088896340736f;
 constexpr float kLn2 = 0.69314718055994530942f;
 constexpr uint32_t kSignBit = 0x80000000u;
@@ -55,29 +64,46 @@ struct Seg {
     uint32_t sA, sM; // sign words
 };
 
-__device__ __forceinline__ Seg seg_identity() { return Seg{0.0f, -INFINITY, 0u, 0u}; }
+template <int DOM>
+__device__ __forceinline__ Seg seg_identity()
+{
+    return DOM == kLinear ? Seg{1.0f, 0.0f, 0u, 0u} : Seg{0.0f, -INFINITY, 0u, 0u};
+}
 
-template <bool SIGNED>
+template <int DOM>
 __device__ __forceinline__ Seg seg_combine(const Seg &g1, const Seg &g2)
 {
+    constexpr bool SIGNED = DOM == kSigned;
     Seg r;
+    if (DOM == kLinear) {
+        r.A = g1.A * g2.A;
+        r.M = g1.M * g2.A + g2.M;
+        r.sA = r.sM = 0u;
+        return r;
+    }
     r.A = g1.A + g2.A;
     r.sA = SIGNED ? (g1.sA ^ g2.sA) : 0u;
     slae<SIGNED>(g1.M + g2.A, SIGNED ? (g1.sM ^ g2.sA) : 0u, g2.M, g2.sM, r.M, r.sM);
     return r;
 }
 
-// State = (log2|x|, sign).  Applying a segment to the state at its start gives the state at its end:
+// State = (log2|x|, sign); in the linear domain lx holds x itself.  Applying a segment to the state at its start gives the state at its end:
 //   log2|x_e| = slae(log2|x_s| + A, M)       (Eq. (1) with x_0 := x_s, i.e. Sec. 4's cat(log x_0, .))
 struct State {
     float lx;
     uint32_t s;
 };
 
-template <bool SIGNED>
+template <int DOM>
 __device__ __forceinline__ State seg_apply(const State &x, const Seg &g)
 {
+    constexpr bool SIGNED = DOM == kSigned;
     State r;
+    if (DOM == kLinear) {
+        r.lx = x.lx * g.A + g.M;
+        r.s = 0u;
+        return r;
+    }
     slae<SIGNED>(x.lx + g.A, SIGNED ? (x.s ^ g.sA) : 0u, g.M, g.sM, r.lx, r.s);
     return r;
 }
@@ -88,10 +114,14 @@ __device__ __forceinline__ float widen(float v) { return v; }
 __device__ __forceinline__ float widen(uint16_t bf16_bits) { return u2f((uint32_t)bf16_bits << 16); }
 
 // log2|v| and sign of a stored input value.  LOG_IN: v is a natural log of a positive number.
-template <bool SIGNED, bool LOG_IN>
+template <int DOM, bool LOG_IN>
 __device__ __forceinline__ void encode(float v, float &l, uint32_t &s)
 {
-    if (LOG_IN) {
+    constexpr bool SIGNED = DOM == kSigned;
+    if (DOM == kLinear) {
+        l = v;
+        s = 0;
+    } else if (LOG_IN) {
         l = v * kLog2e;
         s = 0;
     } else if (SIGNED) {
@@ -101,6 +131,22 @@ __device__ __forceinline__ void encode(float v, float &l, uint32_t &s)
         l = log2_hw(v);
         s = 0;
     }
+}
+
+// Extends the running summary of a lane's steps by one encoded step (la, sa), (lb, sb).
+template <int DOM>
+__device__ __forceinline__ void seg_step(Seg &run, float la, uint32_t sa, float lb, uint32_t sb)
+{
+    constexpr bool SIGNED = DOM == kSigned;
+    if (DOM == kLinear) {
+        run.M = run.M * la + lb;
+        run.A *= la;
+        return;
+    }
+    const uint32_t sp = SIGNED ? (run.sM ^ sa) : 0u;
+    slae<SIGNED>(run.M + la, sp, lb, sb, run.M, run.sM);
+    run.A += la;
+    if (SIGNED) run.sA ^= sa;
 }
 
 // ---- per-element record between the scan and the emit ------------------------------------------------
@@ -115,11 +161,14 @@ __device__ __forceinline__ void encode(float v, float &l, uint32_t &s)
 //                  `sw` and of `sm`.
 // The first term is formed in the log domain so that a large local product times a small state (or
 // the reverse) does not overflow or flush on the way.
-template <bool SIGNED, bool LOG_OUT>
+template <int DOM, bool LOG_OUT>
 __device__ __forceinline__ void stash(const Seg &run, int k, float &r0, float &r1, uint32_t &sw, uint32_t &sm)
 {
+    constexpr bool SIGNED = DOM == kSigned;
     r0 = run.A;
-    if (LOG_OUT) {
+    if (DOM == kLinear) {
+        r1 = run.M; // x_k = x_s A_k + M_k
+    } else if (LOG_OUT) {
         r1 = run.M;
         if (SIGNED) {
             sw |= (run.sA >> 31) << k;
@@ -137,16 +186,19 @@ __device__ __forceinline__ void stash(const Seg &run, int k, float &r0, float &r
 }
 
 // Folds the sign of the lane's start state into the sign word, once per lane.
-template <bool SIGNED>
+template <int DOM>
 __device__ __forceinline__ uint32_t fold_state_sign(uint32_t sw, const State &x)
 {
+    constexpr bool SIGNED = DOM == kSigned;
     return SIGNED ? (sw ^ (uint32_t)((int32_t)x.s >> 31)) : 0u;
 }
 
 // swx = fold_state_sign(sw, x).
-template <bool SIGNED, bool LOG_OUT>
+template <int DOM, bool LOG_OUT>
 __device__ __forceinline__ float emit(const State &x, float r0, float r1, uint32_t swx, int k)
 {
+    constexpr bool SIGNED = DOM == kSigned;
+    if (DOM == kLinear) return x.lx * r0 + r1;
     if (LOG_OUT) {
         float r;
         uint32_t sr;
@@ -185,55 +237,58 @@ __device__ __forceinline__ uint32_t dpp_u(uint32_t oldv, uint32_t v)
 }
 
 // Segment held by the lane CTRL positions earlier (identity where there is none or the row is masked).
-template <int CTRL, int ROW_MASK, bool SIGNED>
+template <int CTRL, int ROW_MASK, int DOM>
 __device__ __forceinline__ Seg seg_dpp(const Seg &g)
 {
+    constexpr bool SIGNED = DOM == kSigned;
+    const Seg id = seg_identity<DOM>();
     Seg r;
-    r.A = dpp_f<CTRL, ROW_MASK>(0.0f, g.A);
-    r.M = dpp_f<CTRL, ROW_MASK>(-INFINITY, g.M);
+    r.A = dpp_f<CTRL, ROW_MASK>(id.A, g.A);
+    r.M = dpp_f<CTRL, ROW_MASK>(id.M, g.M);
     r.sA = SIGNED ? dpp_u<CTRL, ROW_MASK>(0u, g.sA) : 0u;
     r.sM = SIGNED ? dpp_u<CTRL, ROW_MASK>(0u, g.sM) : 0u;
     return r;
 }
 
 // Inclusive scan over the 64 lanes, lane order = time order (6 steps).
-template <bool SIGNED>
+template <int DOM>
 __device__ __forceinline__ Seg wave_inclusive_scan(Seg g)
 {
-    g = seg_combine<SIGNED>(seg_dpp<0x111, 0xf, SIGNED>(g), g); // row_shr:1
-    g = seg_combine<SIGNED>(seg_dpp<0x112, 0xf, SIGNED>(g), g); // row_shr:2
-    g = seg_combine<SIGNED>(seg_dpp<0x114, 0xf, SIGNED>(g), g); // row_shr:4
-    g = seg_combine<SIGNED>(seg_dpp<0x118, 0xf, SIGNED>(g), g); // row_shr:8
-    g = seg_combine<SIGNED>(seg_dpp<0x142, 0xa, SIGNED>(g), g); // row_bcast:15 into rows 1,3
-    g = seg_combine<SIGNED>(seg_dpp<0x143, 0xc, SIGNED>(g), g); // row_bcast:31 into rows 2,3
+    g = seg_combine<DOM>(seg_dpp<0x111, 0xf, DOM>(g), g); // row_shr:1
+    g = seg_combine<DOM>(seg_dpp<0x112, 0xf, DOM>(g), g); // row_shr:2
+    g = seg_combine<DOM>(seg_dpp<0x114, 0xf, DOM>(g), g); // row_shr:4
+    g = seg_combine<DOM>(seg_dpp<0x118, 0xf, DOM>(g), g); // row_shr:8
+    g = seg_combine<DOM>(seg_dpp<0x142, 0xa, DOM>(g), g); // row_bcast:15 into rows 1,3
+    g = seg_combine<DOM>(seg_dpp<0x143, 0xc, DOM>(g), g); // row_bcast:31 into rows 2,3
     return g;
 }
 
 // Inclusive scan inside each row of 16 lanes (4 steps): lanes 15, 31, 47, 63 end up with the fold of
 // their row, in lane order.
-template <bool SIGNED>
+template <int DOM>
 __device__ __forceinline__ Seg row16_inclusive_scan(Seg g)
 {
-    g = seg_combine<SIGNED>(seg_dpp<0x111, 0xf, SIGNED>(g), g);
-    g = seg_combine<SIGNED>(seg_dpp<0x112, 0xf, SIGNED>(g), g);
-    g = seg_combine<SIGNED>(seg_dpp<0x114, 0xf, SIGNED>(g), g);
-    g = seg_combine<SIGNED>(seg_dpp<0x118, 0xf, SIGNED>(g), g);
+    g = seg_combine<DOM>(seg_dpp<0x111, 0xf, DOM>(g), g);
+    g = seg_combine<DOM>(seg_dpp<0x112, 0xf, DOM>(g), g);
+    g = seg_combine<DOM>(seg_dpp<0x114, 0xf, DOM>(g), g);
+    g = seg_combine<DOM>(seg_dpp<0x118, 0xf, DOM>(g), g);
     return g;
 }
 
 // Inclusive scan inside each half of the wave (5 steps): lanes 31 and 63 end up with the fold of lanes
 // 0..31 and 32..63, in lane order.
-template <bool SIGNED>
+template <int DOM>
 __device__ __forceinline__ Seg half_inclusive_scan(Seg g)
 {
-    g = row16_inclusive_scan<SIGNED>(g);
-    g = seg_combine<SIGNED>(seg_dpp<0x142, 0xa, SIGNED>(g), g); // row_bcast:15 into rows 1,3
+    g = row16_inclusive_scan<DOM>(g);
+    g = seg_combine<DOM>(seg_dpp<0x142, 0xa, DOM>(g), g); // row_bcast:15 into rows 1,3
     return g;
 }
 
-template <bool SIGNED>
+template <int DOM>
 __device__ __forceinline__ Seg seg_readlane(const Seg &g, int lane)
 {
+    constexpr bool SIGNED = DOM == kSigned;
     Seg r;
     r.A = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(g.A), lane));
     r.M = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(g.M), lane));
@@ -243,10 +298,10 @@ __device__ __forceinline__ Seg seg_readlane(const Seg &g, int lane)
 }
 
 // Exclusive version of an inclusive result: lane i receives lane i-1's value, lane 0 the identity.
-template <bool SIGNED>
+template <int DOM>
 __device__ __forceinline__ Seg wave_shift_up(const Seg &g)
 {
-    return seg_dpp<0x138, 0xf, SIGNED>(g); // wave_shr:1
+    return seg_dpp<0x138, 0xf, DOM>(g); // wave_shr:1
 }
 
 __device__ __forceinline__ float readlane_f(float v, int lane)
@@ -283,15 +338,17 @@ __device__ __forceinline__ uint32_t rec_payload(rec_t r) { return (uint32_t)r; }
 __device__ __forceinline__ uint32_t rec_bits(rec_t r) { return (uint32_t)(r >> 32) & 3u; }
 
 // A segment summary is two records: {A, tag | sA, sM} and {M, tag}.
-template <bool SIGNED>
+template <int DOM>
 __device__ __forceinline__ void seg_put(rec_t *pa, rec_t *pm, const Seg &g, uint32_t epoch)
 {
+    constexpr bool SIGNED = DOM == kSigned;
     rec_put(pa, f2u(g.A), epoch, SIGNED ? ((g.sA >> 31) | ((g.sM >> 31) << 1)) : 0u);
     rec_put(pm, f2u(g.M), epoch, 0u);
 }
-template <bool SIGNED>
+template <int DOM>
 __device__ __forceinline__ Seg seg_from(rec_t ra, rec_t rm)
 {
+    constexpr bool SIGNED = DOM == kSigned;
     Seg g;
     g.A = u2f(rec_payload(ra));
     g.M = u2f(rec_payload(rm));

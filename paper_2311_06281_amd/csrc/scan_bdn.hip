@@ -46,7 +46,7 @@ __device__ __forceinline__ void lane_load(const InT *arow, const InT *brow, int6
 
 // Encodes and scans the lane's elements serially.  On return Av[k], Mv[k] and bit k of sw (and of sm)
 // hold the per-element records (see stash); the summary of all ITEMS steps is returned.
-template <bool SIGNED, bool LOG_IN, bool LOG_OUT, int ITEMS>
+template <int DOM, bool LOG_IN, bool LOG_OUT, int ITEMS>
 __device__ __forceinline__ Seg lane_scan(float (&Av)[ITEMS], float (&Mv)[ITEMS], uint32_t &sw, uint32_t &sm)
 {
     static_assert(ITEMS <= 32, "sign bits are kept in one word");
@@ -56,17 +56,14 @@ __device__ __forceinline__ Seg lane_scan(float (&Av)[ITEMS], float (&Mv)[ITEMS],
     for (int k = 0; k < ITEMS; ++k) {
         float la, lb;
         uint32_t sa, sb;
-        encode<SIGNED, LOG_IN>(Av[k], la, sa);
-        encode<SIGNED, LOG_IN>(Mv[k], lb, sb);
+        encode<DOM, LOG_IN>(Av[k], la, sa);
+        encode<DOM, LOG_IN>(Mv[k], lb, sb);
         if (k == 0) {
             run = Seg{la, lb, sa, sb};
         } else {
-            uint32_t sp = SIGNED ? (run.sM ^ sa) : 0u;
-            slae<SIGNED>(run.M + la, sp, lb, sb, run.M, run.sM);
-            run.A += la;
-            if (SIGNED) run.sA ^= sa;
+            seg_step<DOM>(run, la, sa, lb, sb);
         }
-        stash<SIGNED, LOG_OUT>(run, k, Av[k], Mv[k], sw, sm);
+        stash<DOM, LOG_OUT>(run, k, Av[k], Mv[k], sw, sm);
     }
     return run;
 }
@@ -184,11 +181,12 @@ __device__ __forceinline__ void unpack_inputs(const u32x4 (&v)[NVI], float (&x)[
 
 
 // Element-wise fallback: emits the lane's elements given the state at the lane's first step.
-template <bool SIGNED, bool LOG_OUT, int ITEMS>
+template <int DOM, bool LOG_OUT, int ITEMS>
 __device__ __forceinline__ void lane_emit(float *orow, int64_t start, int64_t n, const State &st,
                                           const float (&Av)[ITEMS], const float (&Mv)[ITEMS], uint32_t sw, uint32_t sm)
 {
-    const uint32_t swx = fold_state_sign<SIGNED>(sw, st);
+    constexpr bool SIGNED = DOM == kSigned;
+    const uint32_t swx = fold_state_sign<DOM>(sw, st);
 #pragma unroll
     for (int k = 0; k < ITEMS; ++k) {
         if constexpr (SIGNED && LOG_OUT) {
@@ -199,7 +197,7 @@ __device__ __forceinline__ void lane_emit(float *orow, int64_t start, int64_t n,
                 orow[2 * (start + k) + 1] = im;
             }
         } else {
-            const float o = emit<SIGNED, LOG_OUT>(st, Av[k], Mv[k], swx, k);
+            const float o = emit<DOM, LOG_OUT>(st, Av[k], Mv[k], swx, k);
             if (start + k < n) orow[start + k] = o;
         }
     }
@@ -234,9 +232,10 @@ __device__ __forceinline__ void wave_emit_clog_blocked(float *orow, int64_t n_el
     }
 }
 
-template <bool SIGNED, bool LOG_IN, bool LOG_OUT, typename InT, int ITEMS, bool VECIO>
+template <int DOM, bool LOG_IN, bool LOG_OUT, typename InT, int ITEMS, bool VECIO>
 __global__ __launch_bounds__(256, VECIO ? 4 : 1) void heinsen_scan_rows_wave(RowsParams p)
 {
+    constexpr bool SIGNED = DOM == kSigned;
     // 16-byte slots per wave: the output row (ITEMS/4 vectors per lane, the larger of the two) plus padding
     __shared__ u32x4 stage[VECIO ? 4 : 1][VECIO ? 64 * (ITEMS / 4 + 1) : 1];
     const int lane = threadIdx.x & 63;
@@ -268,26 +267,26 @@ __global__ __launch_bounds__(256, VECIO ? 4 : 1) void heinsen_scan_rows_wave(Row
     } else {
         lane_load<LOG_IN, InT, ITEMS>(arow, brow, start, p.n, Av, Mv);
     }
-    Seg mine = lane_scan<SIGNED, LOG_IN, LOG_OUT, ITEMS>(Av, Mv, sw, sm);
-    Seg excl = wave_shift_up<SIGNED>(wave_inclusive_scan<SIGNED>(mine));
+    Seg mine = lane_scan<DOM, LOG_IN, LOG_OUT, ITEMS>(Av, Mv, sw, sm);
+    Seg excl = wave_shift_up<DOM>(wave_inclusive_scan<DOM>(mine));
 
     State st;
-    encode<SIGNED, LOG_IN>(p.x0[p.x0_stride ? row : 0], st.lx, st.s);
-    st = seg_apply<SIGNED>(st, excl);
+    encode<DOM, LOG_IN>(p.x0[p.x0_stride ? row : 0], st.lx, st.s);
+    st = seg_apply<DOM>(st, excl);
     if constexpr (VECIO && SIGNED && LOG_OUT) {
         wave_emit_clog_blocked<ITEMS>(orow, p.n, stage[w], lane, st, Av, Mv, sw, sm);
     } else if (VECIO) {
         constexpr int NVO = ITEMS / 4;
-        const uint32_t swx = fold_state_sign<SIGNED>(sw, st);
+        const uint32_t swx = fold_state_sign<DOM>(sw, st);
         u32x4 vo[NVO];
 #pragma unroll
         for (int q = 0; q < NVO; ++q)
 #pragma unroll
             for (int i = 0; i < 4; ++i)
-                vo[q][i] = f2u(emit<SIGNED, LOG_OUT>(st, Av[q * 4 + i], Mv[q * 4 + i], swx, q * 4 + i));
+                vo[q][i] = f2u(emit<DOM, LOG_OUT>(st, Av[q * 4 + i], Mv[q * 4 + i], swx, q * 4 + i));
         wave_store_blocked<NVO>(reinterpret_cast<u32x4 *>(orow), p.n / 4, stage[w], lane, vo);
     } else {
-        lane_emit<SIGNED, LOG_OUT, ITEMS>(orow, start, p.n, st, Av, Mv, sw, sm);
+        lane_emit<DOM, LOG_OUT, ITEMS>(orow, start, p.n, st, Av, Mv, sw, sm);
     }
 }
 
@@ -343,9 +342,11 @@ struct State64 {
 
 // seg_apply with the state kept in float64: only the (small) correction log2(1 +- 2^-|t|) is formed in
 // float32, so a long chain does not accumulate float32 rounding of the state itself.
-template <bool SIGNED>
+template <int DOM>
 __device__ __forceinline__ State64 seg_apply64(const State64 &x, const Seg &g)
 {
+    constexpr bool SIGNED = DOM == kSigned;
+    if (DOM == kLinear) return State64{x.lx * (double)g.A + (double)g.M, 0u};
     const double p = x.lx + (double)g.A;
     const double q = (double)g.M;
     const uint32_t sp = SIGNED ? (x.s ^ g.sA) : 0u;
@@ -363,9 +364,10 @@ __device__ __forceinline__ State64 seg_apply64(const State64 &x, const Seg &g)
     return r;
 }
 
-template <bool SIGNED, bool LOG_IN, bool LOG_OUT, typename InT, bool VECIO, bool MULTI>
+template <int DOM, bool LOG_IN, bool LOG_OUT, typename InT, bool VECIO, bool MULTI>
 __global__ __launch_bounds__(kTileWaves * 64) void heinsen_scan_tiles(TileParams p)
 {
+    constexpr bool SIGNED = DOM == kSigned;
     constexpr int NW = kTileWaves;
     constexpr int ITEMS = kTileItems;
     __shared__ uint32_t s_tile;
@@ -445,9 +447,9 @@ __global__ __launch_bounds__(kTileWaves * 64) void heinsen_scan_tiles(TileParams
     } else {
         lane_load<LOG_IN, InT, ITEMS>(arow, brow, start, p.n, Av, Mv);
     }
-    Seg mine = lane_scan<SIGNED, LOG_IN, LOG_OUT, ITEMS>(Av, Mv, sw, sm);
-    Seg incl = wave_inclusive_scan<SIGNED>(mine);
-    Seg lane_excl = wave_shift_up<SIGNED>(incl);
+    Seg mine = lane_scan<DOM, LOG_IN, LOG_OUT, ITEMS>(Av, Mv, sw, sm);
+    Seg incl = wave_inclusive_scan<DOM>(mine);
+    Seg lane_excl = wave_shift_up<DOM>(incl);
     HS_STAMP(1);
     if (lane == 63) {
         lds_A[w] = incl.A;
@@ -457,8 +459,8 @@ __global__ __launch_bounds__(kTileWaves * 64) void heinsen_scan_tiles(TileParams
     __syncthreads();
 
     // summary of the waves before this one, and (wave 0) of the whole tile, in wave order
-    Seg wave_excl = seg_identity();
-    Seg total = seg_identity();
+    Seg wave_excl = seg_identity<DOM>();
+    Seg total = seg_identity<DOM>();
 #pragma unroll
     for (int j = 0; j < NW; ++j) {
         Seg h;
@@ -466,7 +468,7 @@ __global__ __launch_bounds__(kTileWaves * 64) void heinsen_scan_tiles(TileParams
         h.M = lds_M[j];
         h.sA = SIGNED ? (lds_S[j] << 31) : 0u;
         h.sM = SIGNED ? (lds_S[j] << 30) : 0u;
-        total = (j == 0) ? h : seg_combine<SIGNED>(total, h);
+        total = (j == 0) ? h : seg_combine<DOM>(total, h);
         if (j + 1 == w) wave_excl = total;
     }
 
@@ -474,28 +476,28 @@ __global__ __launch_bounds__(kTileWaves * 64) void heinsen_scan_tiles(TileParams
         State64 st;
         {
             float lx;
-            encode<SIGNED, LOG_IN>(p.x0[p.x0_stride ? row : 0], lx, st.s);
+            encode<DOM, LOG_IN>(p.x0[p.x0_stride ? row : 0], lx, st.s);
             st.lx = (double)lx;
         }
         HS_STAMP(2);
         if (MULTI) {
-            if (more && r < 31u && lane == 0) seg_put<SIGNED>(rrow + 2 * (size_t)c, rrow + 2 * (size_t)c + 1, total, p.epoch);
+            if (more && r < 31u && lane == 0) seg_put<DOM>(rrow + 2 * (size_t)c, rrow + 2 * (size_t)c + 1, total, p.epoch);
             // The last tile of a group owes the later groups the summary of its group; it needs level 1
             // only and is published as soon as that is in, whatever else is still on its way.
             const bool lead = more && r == 31u;
             bool pub2 = !lead;
-            Seg f1 = seg_identity(), f2 = seg_identity(), a2 = seg_identity();
+            Seg f1 = seg_identity<DOM>(), f2 = seg_identity<DOM>(), a2 = seg_identity<DOM>();
             const uint64_t m1 = 0x7fffffff00000000ull, all = ~0ull;
             for (;;) {
                 if ((!pub2 && (have & m1) == m1) || have == all) {
-                    Seg part = (need && got && lane != 31) ? seg_from<SIGNED>(ra, rm) : seg_identity();
-                    part = half_inclusive_scan<SIGNED>(part);
-                    f2 = seg_readlane<SIGNED>(part, 31);
-                    f1 = seg_readlane<SIGNED>(part, 63);
+                    Seg part = (need && got && lane != 31) ? seg_from<DOM>(ra, rm) : seg_identity<DOM>();
+                    part = half_inclusive_scan<DOM>(part);
+                    f2 = seg_readlane<DOM>(part, 31);
+                    f1 = seg_readlane<DOM>(part, 63);
                     if (!pub2) {
-                        a2 = seg_combine<SIGNED>(f1, total); // this group of 32 tiles
+                        a2 = seg_combine<DOM>(f1, total); // this group of 32 tiles
                         if (g < 31u && lane == 0)
-                            seg_put<SIGNED>(rrow + p.off2 + 2 * (size_t)(c >> 5), rrow + p.off2 + 2 * (size_t)(c >> 5) + 1, a2, p.epoch);
+                            seg_put<DOM>(rrow + p.off2 + 2 * (size_t)(c >> 5), rrow + p.off2 + 2 * (size_t)(c >> 5) + 1, a2, p.epoch);
                         pub2 = true;
                     }
                 }
@@ -513,16 +515,16 @@ __global__ __launch_bounds__(kTileWaves * 64) void heinsen_scan_tiles(TileParams
                 st.lx = __longlong_as_double((long long)(((unsigned long long)hi << 32) | lo));
                 st.s = SIGNED ? (sg << 31) : 0u;
             }
-            const State64 st2 = seg_apply64<SIGNED>(st, f2); // state at the start of the group
+            const State64 st2 = seg_apply64<DOM>(st, f2); // state at the start of the group
             if (lead && g == 31u) {
-                const State64 nx = seg_apply64<SIGNED>(st2, a2); // start of the next super-block
+                const State64 nx = seg_apply64<DOM>(st2, a2); // start of the next super-block
                 const unsigned long long bits = (unsigned long long)__double_as_longlong(nx.lx);
                 if (lane == 0) {
                     rec_put(rrow + p.off4 + 2 * (size_t)(sb + 1), (uint32_t)(bits >> 32), p.epoch, SIGNED ? (nx.s >> 31) : 0u);
                     rec_put(rrow + p.off4 + 2 * (size_t)(sb + 1) + 1, (uint32_t)bits, p.epoch, 0u);
                 }
             }
-            st = seg_apply64<SIGNED>(st2, f1);
+            st = seg_apply64<DOM>(st2, f1);
         }
         HS_STAMP(4);
         if (lane == 0) {
@@ -536,25 +538,25 @@ __global__ __launch_bounds__(kTileWaves * 64) void heinsen_scan_tiles(TileParams
     State st;
     st.lx = lds_startL;
     st.s = lds_startS;
-    st = seg_apply<SIGNED>(st, seg_combine<SIGNED>(wave_excl, lane_excl));
+    st = seg_apply<DOM>(st, seg_combine<DOM>(wave_excl, lane_excl));
     constexpr int OW = (SIGNED && LOG_OUT) ? 2 : 1; // floats per output element
     float *orow = p.out + OW * row * p.n;
     if constexpr (VECIO && SIGNED && LOG_OUT) {
         wave_emit_clog_blocked<ITEMS>(orow + OW * wstart, p.n - wstart, stage[w], lane, st, Av, Mv, sw, sm);
     } else if (VECIO) {
         constexpr int NVO = ITEMS / 4;
-        const uint32_t swx = fold_state_sign<SIGNED>(sw, st);
+        const uint32_t swx = fold_state_sign<DOM>(sw, st);
         u32x4 vo[NVO];
 #pragma unroll
         for (int qv = 0; qv < NVO; ++qv)
 #pragma unroll
             for (int i = 0; i < 4; ++i)
-                vo[qv][i] = f2u(emit<SIGNED, LOG_OUT>(st, Av[qv * 4 + i], Mv[qv * 4 + i], swx, qv * 4 + i));
+                vo[qv][i] = f2u(emit<DOM, LOG_OUT>(st, Av[qv * 4 + i], Mv[qv * 4 + i], swx, qv * 4 + i));
         int64_t n_vec = (p.n - wstart) / 4;
         n_vec = n_vec < 0 ? 0 : n_vec;
         wave_store_blocked<NVO>(reinterpret_cast<u32x4 *>(orow + wstart), n_vec, stage[w], lane, vo);
     } else {
-        lane_emit<SIGNED, LOG_OUT, ITEMS>(orow, start, p.n, st, Av, Mv, sw, sm);
+        lane_emit<DOM, LOG_OUT, ITEMS>(orow, start, p.n, st, Av, Mv, sw, sm);
     }
     HS_STAMP(6);
     HS_STAMP(7);
@@ -599,7 +601,7 @@ BdnPlan make_plan(const ScanCall &c)
     return pl;
 }
 
-template <bool SIGNED, bool LOG_IN, bool LOG_OUT, typename InT>
+template <int DOM, bool LOG_IN, bool LOG_OUT, typename InT>
 hipError_t launch_mode(const ScanCall &c, const BdnPlan &pl, rec_t *records, LaunchTag tag)
 {
     if (pl.wave_kernel) {
@@ -613,7 +615,7 @@ hipError_t launch_mode(const ScanCall &c, const BdnPlan &pl, rec_t *records, Lau
         p.x0_stride = c.x0_scalar ? 0 : 1;
         dim3 grid((unsigned)ceil_div(pl.rows, 4)), block(256);
 #define HS_ROWS(ITEMS_, VEC_)                                                                            \
-    hipLaunchKernelGGL((heinsen_scan_rows_wave<SIGNED, LOG_IN, LOG_OUT, InT, ITEMS_, VEC_>), grid, block, 0, \
+    hipLaunchKernelGGL((heinsen_scan_rows_wave<DOM, LOG_IN, LOG_OUT, InT, ITEMS_, VEC_>), grid, block, 0, \
                        c.stream, p)
         if (pl.vecio) {
             if (pl.items == 32) HS_ROWS(32, true);
@@ -650,7 +652,7 @@ hipError_t launch_mode(const ScanCall &c, const BdnPlan &pl, rec_t *records, Lau
 #endif
     dim3 grid(pl.ntiles), block(kTileWaves * 64);
 #define HS_TILES(VEC_, MULTI_) \
-    hipLaunchKernelGGL((heinsen_scan_tiles<SIGNED, LOG_IN, LOG_OUT, InT, VEC_, MULTI_>), grid, block, 0, c.stream, p)
+    hipLaunchKernelGGL((heinsen_scan_tiles<DOM, LOG_IN, LOG_OUT, InT, VEC_, MULTI_>), grid, block, 0, c.stream, p)
     if (pl.vecio) {
         if (pl.multi) HS_TILES(true, true);
         else HS_TILES(true, false);

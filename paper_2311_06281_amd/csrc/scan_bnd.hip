@@ -98,9 +98,10 @@ __device__ __forceinline__ void unpack_signs(uint32_t s, Seg &g)
 // VEC channels per lane, T steps per wave, NW waves per workgroup, G tiles per group along time,
 // MINW waves per SIMD the register allocation must allow, SB: keep the scheduler from hoisting work
 // across time steps (bounds register pressure).
-template <bool SIGNED, bool LOG_IN, bool LOG_OUT, typename InT, int VEC, int T, int NW, int G, int MINW, bool SB>
+template <int DOM, bool LOG_IN, bool LOG_OUT, typename InT, int VEC, int T, int NW, int G, int MINW, bool SB>
 __global__ __launch_bounds__(NW * 64, MINW) void heinsen_scan_bnd(BndParams p)
 {
+    constexpr bool SIGNED = DOM == kSigned;
     constexpr int CH = 64 * VEC;
     constexpr int GP = G > 1 ? G - 1 : 1;
     static_assert(T <= 32, "one sign word per channel");
@@ -220,17 +221,14 @@ __global__ __launch_bounds__(NW * 64, MINW) void heinsen_scan_bnd(BndParams p)
         for (int v = 0; v < VEC; ++v) {
             float la, lb;
             uint32_t sa, sb;
-            encode<SIGNED, LOG_IN>(Av[k][v], la, sa);
-            encode<SIGNED, LOG_IN>(Mv[k][v], lb, sb);
+            encode<DOM, LOG_IN>(Av[k][v], la, sa);
+            encode<DOM, LOG_IN>(Mv[k][v], lb, sb);
             if (k == 0) {
                 run[v] = Seg{la, lb, sa, sb};
             } else {
-                uint32_t sp = SIGNED ? (run[v].sM ^ sa) : 0u;
-                slae<SIGNED>(run[v].M + la, sp, lb, sb, run[v].M, run[v].sM);
-                run[v].A += la;
-                if (SIGNED) run[v].sA ^= sa;
+                seg_step<DOM>(run[v], la, sa, lb, sb);
             }
-            stash<SIGNED, LOG_OUT>(run[v], k, Av[k][v], Mv[k][v], sw[v], sm[v]);
+            stash<DOM, LOG_OUT>(run[v], k, Av[k][v], Mv[k][v], sw[v], sm[v]);
         }
         if (SB) __builtin_amdgcn_sched_barrier(0);
     }
@@ -266,7 +264,7 @@ __global__ __launch_bounds__(NW * 64, MINW) void heinsen_scan_bnd(BndParams p)
                 h.M = lds_M[j][loff + v];
                 h.sA = h.sM = 0u;
                 if (SIGNED) unpack_signs(lds_S[j][loff + v], h);
-                acc = seg_combine<SIGNED>(acc, h);
+                acc = seg_combine<DOM>(acc, h);
             }
             pre[v] = acc;
         }
@@ -278,7 +276,7 @@ __global__ __launch_bounds__(NW * 64, MINW) void heinsen_scan_bnd(BndParams p)
         if (more && r < G - 1) {
             rec_t *tp = p.agg + (size_t)tile * (2 * CH) + loff;
 #pragma unroll
-            for (int v = 0; v < VEC; ++v) seg_put<SIGNED>(tp + v, tp + CH + v, pre[v], p.epoch);
+            for (int v = 0; v < VEC; ++v) seg_put<DOM>(tp + v, tp + CH + v, pre[v], p.epoch);
         }
         HS_STAMP(3);
         if (!have_records) {
@@ -294,7 +292,7 @@ __global__ __launch_bounds__(NW * 64, MINW) void heinsen_scan_bnd(BndParams p)
             if (g == 0) {
                 float x0v = LOG_IN ? 0.0f : 1.0f;
                 if (chan_ok) x0v = p.x0[p.x0_stride ? ((int64_t)bidx * p.D + d0 + v) : 0];
-                encode<SIGNED, LOG_IN>(x0v, st[v].lx, st[v].s);
+                encode<DOM, LOG_IN>(x0v, st[v].lx, st[v].s);
             } else {
                 st[v].lx = u2f(rec_payload(rS[v]));
                 st[v].s = SIGNED ? (rec_bits(rS[v]) << 31) : 0u;
@@ -305,7 +303,7 @@ __global__ __launch_bounds__(NW * 64, MINW) void heinsen_scan_bnd(BndParams p)
         for (int j = 0; j < G - 1; ++j) {
             if (j < r) {
 #pragma unroll
-                for (int v = 0; v < VEC; ++v) st[v] = seg_apply<SIGNED>(st[v], seg_from<SIGNED>(rA[j][v], rM[j][v]));
+                for (int v = 0; v < VEC; ++v) st[v] = seg_apply<DOM>(st[v], seg_from<DOM>(rA[j][v], rM[j][v]));
             }
         }
 #pragma unroll
@@ -319,7 +317,7 @@ __global__ __launch_bounds__(NW * 64, MINW) void heinsen_scan_bnd(BndParams p)
             rec_t *sp = p.state + ((size_t)(g + 1) * p.ncols + col) * CH + loff;
 #pragma unroll
             for (int v = 0; v < VEC; ++v) {
-                State nx = seg_apply<SIGNED>(st[v], pre[v]);
+                State nx = seg_apply<DOM>(st[v], pre[v]);
                 rec_put(sp + v, f2u(nx.lx), p.epoch, SIGNED ? (nx.s >> 31) : 0u);
             }
         }
@@ -333,14 +331,14 @@ __global__ __launch_bounds__(NW * 64, MINW) void heinsen_scan_bnd(BndParams p)
     for (int v = 0; v < VEC; ++v) {
         st[v].lx = lds_startL[loff + v];
         st[v].s = lds_startS[loff + v];
-        if (w > 0) st[v] = seg_apply<SIGNED>(st[v], pre[v]);
+        if (w > 0) st[v] = seg_apply<DOM>(st[v], pre[v]);
     }
     constexpr int OW = (SIGNED && LOG_OUT) ? 2 : 1; // floats per output element
     float *op = p.out + OW * ubase;
     const bool full = chan_ok && t0 + T <= p.n;
     uint32_t swx[VEC];
 #pragma unroll
-    for (int v = 0; v < VEC; ++v) swx[v] = fold_state_sign<SIGNED>(sw[v], st[v]);
+    for (int v = 0; v < VEC; ++v) swx[v] = fold_state_sign<DOM>(sw[v], st[v]);
 #pragma unroll
     for (int k = 0; k < T; ++k) {
         if constexpr (SIGNED && LOG_OUT) {
@@ -352,7 +350,7 @@ __global__ __launch_bounds__(NW * 64, MINW) void heinsen_scan_bnd(BndParams p)
         } else {
             float o[VEC];
 #pragma unroll
-            for (int v = 0; v < VEC; ++v) o[v] = emit<SIGNED, LOG_OUT>(st[v], Av[k][v], Mv[k][v], swx[v], k);
+            for (int v = 0; v < VEC; ++v) o[v] = emit<DOM, LOG_OUT>(st[v], Av[k][v], Mv[k][v], swx[v], k);
             if (full || (chan_ok && t0 + k < p.n)) store_vec(op + (int64_t)k * p.D + loff, o, p.stream_out != 0);
         }
         if (SB) __builtin_amdgcn_sched_barrier(0);
@@ -439,9 +437,10 @@ BndPlan make_plan(const ScanCall &c)
     return pl;
 }
 
-template <bool SIGNED, bool LOG_IN, bool LOG_OUT, typename InT>
+template <int DOM, bool LOG_IN, bool LOG_OUT, typename InT>
 hipError_t launch_mode(const ScanCall &c, const BndPlan &pl, rec_t *records, LaunchTag tag)
 {
+    constexpr bool SIGNED = DOM == kSigned;
     BndParams p;
     p.a = c.a;
     p.b = c.b;
@@ -469,7 +468,7 @@ hipError_t launch_mode(const ScanCall &c, const BndPlan &pl, rec_t *records, Lau
     if constexpr (SIGNED && sizeof(InT) == 4) {
 #define X(ID, V, T_, NW_, G_, MW, SB_)                                                                                 \
     if (pl.variant == ID) {                                                                                            \
-        hipLaunchKernelGGL((heinsen_scan_bnd<SIGNED, LOG_IN, LOG_OUT, InT, V, T_, NW_, G_, MW, SB_>), grid, block, 0,  \
+        hipLaunchKernelGGL((heinsen_scan_bnd<DOM, LOG_IN, LOG_OUT, InT, V, T_, NW_, G_, MW, SB_>), grid, block, 0,  \
                            c.stream, p);                                                                               \
         return hipGetLastError();                                                                                      \
     }
@@ -478,12 +477,12 @@ hipError_t launch_mode(const ScanCall &c, const BndPlan &pl, rec_t *records, Lau
     }
 #endif
     if constexpr (SIGNED && LOG_OUT) {
-        hipLaunchKernelGGL((heinsen_scan_bnd<SIGNED, LOG_IN, LOG_OUT, InT, 1, 16, 16, 4, 4, true>), grid, block, 0, c.stream, p);
+        hipLaunchKernelGGL((heinsen_scan_bnd<DOM, LOG_IN, LOG_OUT, InT, 1, 16, 16, 4, 4, true>), grid, block, 0, c.stream, p);
     } else {
         if (pl.vec == 2)
-            hipLaunchKernelGGL((heinsen_scan_bnd<SIGNED, LOG_IN, LOG_OUT, InT, 2, 16, 8, 4, 4, true>), grid, block, 0, c.stream, p);
+            hipLaunchKernelGGL((heinsen_scan_bnd<DOM, LOG_IN, LOG_OUT, InT, 2, 16, 8, 4, 4, true>), grid, block, 0, c.stream, p);
         else
-            hipLaunchKernelGGL((heinsen_scan_bnd<SIGNED, LOG_IN, LOG_OUT, InT, 1, 32, 8, 4, 4, true>), grid, block, 0, c.stream, p);
+            hipLaunchKernelGGL((heinsen_scan_bnd<DOM, LOG_IN, LOG_OUT, InT, 1, 32, 8, 4, 4, true>), grid, block, 0, c.stream, p);
     }
     return hipGetLastError();
 }

@@ -62,6 +62,7 @@ P = 4096  # a non-null, aligned fake address: validation must fail before it is 
     ((P, P, P, P, 1, 1, 8, 0, hb.HEINSEN_OUT_COMPLEX), hb.HEINSEN_ERR_INVALID_ARG),  # complex output of a linear result
     ((P, P, P, P, 1, 1, 8, 0, hb.HEINSEN_OUT_COMPLEX | hb.HEINSEN_LOG_OUTPUT | hb.HEINSEN_LOG_INPUTS),
      hb.HEINSEN_ERR_UNSUPPORTED),                                       # complex output of log-domain inputs
+    ((P, P, P, P, 1, 1, 8, 0, hb.HEINSEN_LINEAR | hb.HEINSEN_LOG_INPUTS), hb.HEINSEN_ERR_INVALID_ARG),  # linear path on log data
     ((P, P, P, P + 4, 1, 1, 8, 0, hb.HEINSEN_OUT_COMPLEX | hb.HEINSEN_LOG_OUTPUT), hb.HEINSEN_ERR_INVALID_ARG),  # misaligned complex out
 ])
 def test_bad_arguments_are_rejected_on_the_host(args, expect):

@@ -28,7 +28,7 @@ def _inputs(rng, shape, layout, mode):
     """Stored inputs (float32 arrays holding exactly what the GPU reads) for one mode."""
     B = shape[0]
     D = shape[2] if layout == "BND" else shape[1]
-    if mode in ("signed", "signed_clog"):
+    if mode in ("signed", "signed_clog", "linear"):
         a = rng.uniform(-1.1, 1.1, shape)
         b = rng.normal(0, 1, shape)
         x0 = rng.normal(0, 1, B * D)
@@ -50,6 +50,7 @@ MODES = {
     "log": ("LOG_INPUTS",),
     "log_logout": ("LOG_INPUTS", "LOG_OUTPUT"),
     "signed_clog": ("LOG_OUTPUT", "OUT_COMPLEX"),
+    "linear": ("LINEAR",),  # comparison path: same data and bound as the signed log-space path
 }
 SHAPES = {
     "BDN": [(2, 3, 1), (1, 5, 17), (2, 3, 520), (1, 2, 2048), (1, 3, 2056), (1, 1, 16384 * 3 + 8), (3, 2, 16384 + 1)],
@@ -106,7 +107,7 @@ def _check(got, a, b, x0, layout, mode):
     else:
         val = np.exp(got.astype(np.float64)) if mode.endswith("logout") else got.astype(np.float64)
     err = np.abs(val - ref)
-    if mode in ("signed", "signed_clog"):
+    if mode in ("signed", "signed_clog", "linear"):
         # running scale max_{0<=s<=t} |x_s|: it starts at |x_0|, which is a member of the sequence (a first
         # step that cancels, x_1 = a_1 x_0 + b_1 ~ 0, has no other scale to be measured against)
         axis = 1 if layout == "BND" else 2
