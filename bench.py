@@ -24,9 +24,9 @@ if ROOT not in sys.path:
 HBM_PEAK_GBS = 8000.0  # MI355X published HBM3E bandwidth
 
 # HBM bytes per launch measured with rocprofv3 --pmc (FETCH_SIZE, WRITE_SIZE), scaled by the factor a
-# plain copy kernel of known size gives (profiles/heinsen_scan_bnd_cfg2_hbm_traffic.txt): 275.48 MB read +
+# plain copy kernel of known size gives (profiles/heinsen_scan_bnd_cfg2_hbm_traffic.txt): 275.36 MB read +
 # 136.05 MB written per launch of configuration 2.  None for workloads that were not measured.
-MEASURED_TRAFFIC_BYTES = {2: 411528586}
+MEASURED_TRAFFIC_BYTES = {2: 411415143}
 
 
 def device_inputs(cfg, torch, distinct=2):
