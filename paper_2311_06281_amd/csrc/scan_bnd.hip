@@ -114,6 +114,9 @@ __global__ __launch_bounds__(NW * 64, MINW) void heinsen_scan_bnd(BndParams p)
 
     const int lane = threadIdx.x & 63;
     const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6); // wave-uniform, kept in an SGPR
+#ifdef HS_TRACE
+    const unsigned long long t_begin = wall_clock64();
+#endif
 
     // Tiles are handed out in start order, so every tile a workgroup may wait for (same column,
     // earlier chunk => smaller ticket) belongs to a workgroup that is already running.
@@ -278,7 +281,9 @@ __global__ __launch_bounds__(NW * 64, MINW) void heinsen_scan_bnd(BndParams p)
 #pragma unroll
             for (int v = 0; v < VEC; ++v) seg_put<DOM>(tp + v, tp + CH + v, pre[v], p.epoch);
         }
-        HS_STAMP(3);
+#ifdef HS_TRACE
+        if (threadIdx.x == 0) p.trace[(size_t)tile * 8 + 3] = t_begin; // slot 3: workgroup start, before the ticket
+#endif
         if (!have_records) {
             while (!records_in()) {
                 __builtin_amdgcn_s_sleep(2);
@@ -380,7 +385,9 @@ struct BndPlan {
     X(1, 4, 4, 16, 4, 4, true) X(2, 4, 8, 8, 4, 4, true) X(3, 4, 16, 4, 4, 2, true) X(4, 2, 8, 16, 4, 4, true) \
     X(5, 2, 16, 8, 4, 4, true) X(6, 2, 32, 4, 4, 2, true) X(7, 1, 16, 16, 4, 8, true) X(8, 1, 32, 8, 4, 4, true) \
     X(9, 4, 8, 16, 4, 2, true) X(10, 2, 16, 16, 4, 2, true) X(11, 4, 4, 8, 4, 4, true) X(12, 4, 2, 16, 4, 8, true) \
-    X(13, 1, 8, 16, 4, 8, true) X(14, 2, 4, 16, 4, 8, true) X(15, 1, 16, 8, 4, 8, true) X(16, 2, 8, 8, 4, 8, true)
+    X(13, 1, 8, 16, 4, 8, true) X(14, 2, 4, 16, 4, 8, true) X(15, 1, 16, 8, 4, 8, true) X(16, 2, 8, 8, 4, 8, true) \
+    X(17, 1, 32, 4, 4, 4, true) X(18, 1, 16, 4, 4, 8, true) X(19, 1, 8, 8, 4, 8, true) X(20, 1, 32, 8, 8, 4, true) \
+    X(21, 1, 32, 8, 2, 4, true) X(22, 1, 16, 8, 8, 8, true) X(23, 1, 32, 4, 8, 4, true) X(24, 1, 32, 2, 8, 4, true)
 constexpr int kVariants[][4] = {{0, 0, 0, 0},
 #define X(ID, V, T_, NW_, G_, MW, SB_) {V, T_, NW_, G_},
                                 HS_VARIANTS(X)
