@@ -3,7 +3,8 @@
 // Two kernels.
 //  * rows_wave: one wave per row for rows that fit 64*ITEMS elements.  Lane i owns ITEMS consecutive
 //    steps, scans them serially, the 64 lane summaries are scanned with DPP, each lane derives the
-//    state at its first step and emits its elements.  No LDS, no barrier, no global scratch.
+//    state at its first step and emits its elements.  No barrier, no global scratch; LDS only as the
+//    wave's private staging area for coalesced global accesses.
 //  * tiles: rows longer than that are cut into tiles of NW*64*ITEMS elements, one workgroup per
 //    tile: the same lane and wave scans, wave summaries chained through LDS, tile summaries chained
 //    through global memory in a two-level tree (see below); folds happen in a fixed order, so results
@@ -301,7 +302,7 @@ __global__ __launch_bounds__(256, VECIO ? 4 : 1) void heinsen_scan_rows_wave(Row
 // another tile's wait; only the super-block states form a chain, n / (1024 * tile) links long.
 
 constexpr int kTileWaves = 8;   // waves per workgroup
-constexpr int kTileItems = 32;  // elements per lane
+constexpr int kTileItems = 32;  // elements per lane (rows of one tile may use 8 or 16: a shorter serial chain)
 constexpr int kTile = kTileWaves * 64 * kTileItems;
 
 struct TileParams {
@@ -364,12 +365,13 @@ __device__ __forceinline__ State64 seg_apply64(const State64 &x, const Seg &g)
     return r;
 }
 
-template <int DOM, bool LOG_IN, bool LOG_OUT, typename InT, bool VECIO, bool MULTI>
+template <int DOM, bool LOG_IN, bool LOG_OUT, typename InT, bool VECIO, bool MULTI, int ITEMS>
 __global__ __launch_bounds__(kTileWaves * 64) void heinsen_scan_tiles(TileParams p)
 {
     constexpr bool SIGNED = DOM == kSigned;
     constexpr int NW = kTileWaves;
-    constexpr int ITEMS = kTileItems;
+    constexpr int kTile = NW * 64 * ITEMS; // elements per tile
+    static_assert(!MULTI || ITEMS == kTileItems, "rows of several tiles use the full tile");
     __shared__ uint32_t s_tile;
     __shared__ float lds_A[NW], lds_M[NW];
     __shared__ uint32_t lds_S[NW];
@@ -571,6 +573,7 @@ struct BdnPlan {
     int items;    // wave kernel: elements per lane
     bool vecio;
     bool multi;
+    int tile_items; // tiles kernel: elements per lane
     int64_t rows;
     uint32_t tpr, ntiles;
     uint32_t off2, off4, row_stride;
@@ -592,6 +595,8 @@ BdnPlan make_plan(const ScanCall &c)
     pl.tpr = (uint32_t)ceil_div(c.n, kTile);
     pl.ntiles = (uint32_t)(pl.rows * pl.tpr);
     pl.multi = pl.tpr > 1;
+    // a row of one tile is bound by latency: spread it over all waves of the workgroup
+    pl.tile_items = c.n <= kTileWaves * 64 * 8 ? 8 : (c.n <= kTileWaves * 64 * 16 ? 16 : kTileItems);
     if (!pl.multi) return pl;
     const uint32_t n1 = pl.tpr, n2 = (pl.tpr + 31) / 32, n4 = (pl.tpr + 1023) / 1024 + 1;
     pl.off2 = 2 * n1;
@@ -651,14 +656,20 @@ hipError_t launch_mode(const ScanCall &c, const BdnPlan &pl, rec_t *records, Lau
     p.trace = g_trace_bdn;
 #endif
     dim3 grid(pl.ntiles), block(kTileWaves * 64);
-#define HS_TILES(VEC_, MULTI_) \
-    hipLaunchKernelGGL((heinsen_scan_tiles<DOM, LOG_IN, LOG_OUT, InT, VEC_, MULTI_>), grid, block, 0, c.stream, p)
-    if (pl.vecio) {
-        if (pl.multi) HS_TILES(true, true);
-        else HS_TILES(true, false);
+#define HS_TILES(VEC_, MULTI_, ITEMS_) \
+    hipLaunchKernelGGL((heinsen_scan_tiles<DOM, LOG_IN, LOG_OUT, InT, VEC_, MULTI_, ITEMS_>), grid, block, 0, c.stream, p)
+    if (pl.multi) {
+        if (pl.vecio) HS_TILES(true, true, kTileItems);
+        else HS_TILES(false, true, kTileItems);
+    } else if (pl.tile_items == 8) {
+        if (pl.vecio) HS_TILES(true, false, 8);
+        else HS_TILES(false, false, 8);
+    } else if (pl.tile_items == 16) {
+        if (pl.vecio) HS_TILES(true, false, 16);
+        else HS_TILES(false, false, 16);
     } else {
-        if (pl.multi) HS_TILES(false, true);
-        else HS_TILES(false, false);
+        if (pl.vecio) HS_TILES(true, false, kTileItems);
+        else HS_TILES(false, false, kTileItems);
     }
 #undef HS_TILES
     return hipGetLastError();
