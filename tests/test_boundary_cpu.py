@@ -75,3 +75,14 @@ def test_kernel_name_follows_layout_and_length():
     assert hb.heinsen_kernel_name(1, 1, 1 << 26, hb.HEINSEN_LAYOUT_BDN, 8) == "heinsen_scan_tiles"
     with pytest.raises(hb.HeinsenError):
         hb.heinsen_kernel_name(1, 1, 0, 0, 0)
+
+
+def test_bench_refuses_more_than_one_gpu():
+    """bench.py is a one-GPU measurement; asking for more must end with a message, not a wrong number."""
+    import subprocess
+    import sys
+
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    r = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"], capture_output=True, text=True, timeout=120)
+    assert r.returncode != 0
+    assert "ONE GPU" in r.stderr and r.stdout.strip() == ""
