@@ -380,7 +380,8 @@ struct BndPlan {
 };
 
 #ifdef HS_TUNING
-// tuning variants (signed float32 only, development builds): ID, VEC, T, NW, G, MINW, SB
+// tuning variants (development builds; signed float32, or bf16 logs in / logs out with -DHS_TUNING_BF16LOG):
+// ID, VEC, T, NW, G, MINW, SB
 #define HS_VARIANTS(X) \
     X(1, 4, 4, 16, 4, 4, true) X(2, 4, 8, 8, 4, 4, true) X(3, 4, 16, 4, 4, 2, true) X(4, 2, 8, 16, 4, 4, true) \
     X(5, 2, 16, 8, 4, 4, true) X(6, 2, 32, 4, 4, 2, true) X(7, 1, 16, 16, 4, 8, true) X(8, 1, 32, 8, 4, 4, true) \
@@ -399,11 +400,9 @@ constexpr int kNumVariants = sizeof(kVariants) / sizeof(kVariants[0]);
 BndPlan make_plan(const ScanCall &c)
 {
     BndPlan pl;
-    const size_t in_sz = c.bf16 ? 2 : 4;
-    auto aligned = [](const void *ptr, size_t a) { return (reinterpret_cast<uintptr_t>(ptr) % a) == 0; };
-    // float32: one channel per lane, 32 steps per wave, 8 waves (tile = 64 channels x 256 steps, <= 128
-    // VGPRs, two workgroups per CU) measured best on MI355X among the shapes tried; bf16 takes two
-    // channels per lane so that a wave still reads 256 contiguous bytes per step.
+    // One channel per lane, 32 steps per wave, 8 waves (tile = 64 channels x 256 steps, <= 128 VGPRs, two
+    // workgroups per CU) measured best on MI355X among the shapes tried, for float32 and for bf16 storage
+    // (two bf16 channels per lane, which keeps a wave's reads at 256 contiguous bytes, measured 8 % slower).
     pl.vec = 1;
     pl.T = 32;
     pl.NW = 8;
@@ -413,16 +412,17 @@ BndPlan make_plan(const ScanCall &c)
         // and 16 waves keep the tile the same and the kernel free of spills
         pl.T = 16;
         pl.NW = 16;
-    } else if (c.bf16 && c.D % 2 == 0 && aligned(c.a, 2 * in_sz) && aligned(c.b, 2 * in_sz) && aligned(c.out, 8)) {
-        pl.vec = 2;
-        pl.T = 16;
-        pl.NW = 8;
     }
     pl.variant = 0;
 #ifdef HS_TUNING
     if (const char *ev = getenv("HEINSEN_BND_VARIANT")) {
         pl.variant = atoi(ev);
-        if (pl.variant >= 1 && pl.variant < kNumVariants && c.is_signed && !c.bf16 && c.D % 4 == 0) {
+#ifdef HS_TUNING_BF16LOG
+        const bool tuned_mode = !c.is_signed && c.bf16 && c.log_in && c.log_out;
+#else
+        const bool tuned_mode = c.is_signed && !c.log_out && !c.bf16;
+#endif
+        if (pl.variant >= 1 && pl.variant < kNumVariants && tuned_mode && c.D % 4 == 0) {
             pl.vec = kVariants[pl.variant][0];
             pl.T = kVariants[pl.variant][1];
             pl.NW = kVariants[pl.variant][2];
@@ -472,7 +472,12 @@ hipError_t launch_mode(const ScanCall &c, const BndPlan &pl, rec_t *records, Lau
 #endif
     dim3 grid(pl.ntiles), block(pl.NW * 64);
 #ifdef HS_TUNING
-    if constexpr (SIGNED && sizeof(InT) == 4) {
+#ifdef HS_TUNING_BF16LOG
+    constexpr bool kTunedMode = DOM == kPositive && LOG_IN && LOG_OUT && sizeof(InT) == 2;
+#else
+    constexpr bool kTunedMode = SIGNED && !LOG_OUT && sizeof(InT) == 4;
+#endif
+    if constexpr (kTunedMode) {
 #define X(ID, V, T_, NW_, G_, MW, SB_)                                                                                 \
     if (pl.variant == ID) {                                                                                            \
         hipLaunchKernelGGL((heinsen_scan_bnd<DOM, LOG_IN, LOG_OUT, InT, V, T_, NW_, G_, MW, SB_>), grid, block, 0,  \
@@ -486,10 +491,7 @@ hipError_t launch_mode(const ScanCall &c, const BndPlan &pl, rec_t *records, Lau
     if constexpr (SIGNED && LOG_OUT) {
         hipLaunchKernelGGL((heinsen_scan_bnd<DOM, LOG_IN, LOG_OUT, InT, 1, 16, 16, 4, 4, true>), grid, block, 0, c.stream, p);
     } else {
-        if (pl.vec == 2)
-            hipLaunchKernelGGL((heinsen_scan_bnd<DOM, LOG_IN, LOG_OUT, InT, 2, 16, 8, 4, 4, true>), grid, block, 0, c.stream, p);
-        else
-            hipLaunchKernelGGL((heinsen_scan_bnd<DOM, LOG_IN, LOG_OUT, InT, 1, 32, 8, 4, 4, true>), grid, block, 0, c.stream, p);
+        hipLaunchKernelGGL((heinsen_scan_bnd<DOM, LOG_IN, LOG_OUT, InT, 1, 32, 8, 4, 4, true>), grid, block, 0, c.stream, p);
     }
     return hipGetLastError();
 }
