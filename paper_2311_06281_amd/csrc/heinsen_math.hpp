@@ -285,6 +285,28 @@ __device__ __forceinline__ Seg half_inclusive_scan(Seg g)
     return g;
 }
 
+// Inclusive scan inside aligned groups of `group` lanes (a power of two, 1..64): the same six steps, a
+// step taking effect only in lanes that have that many predecessors inside their group.
+template <int DOM>
+__device__ __forceinline__ Seg group_inclusive_scan(Seg g, int lane, int group)
+{
+    const int pos = lane & (group - 1);
+    auto step = [&](const Seg &shifted, bool ok) {
+        const Seg c = seg_combine<DOM>(shifted, g);
+        g.A = ok ? c.A : g.A;
+        g.M = ok ? c.M : g.M;
+        g.sA = ok ? c.sA : g.sA;
+        g.sM = ok ? c.sM : g.sM;
+    };
+    step(seg_dpp<0x111, 0xf, DOM>(g), pos >= 1);
+    step(seg_dpp<0x112, 0xf, DOM>(g), pos >= 2);
+    step(seg_dpp<0x114, 0xf, DOM>(g), pos >= 4);
+    step(seg_dpp<0x118, 0xf, DOM>(g), pos >= 8);
+    step(seg_dpp<0x142, 0xa, DOM>(g), group >= 32); // row_bcast:15 reaches lanes whose pos is >= 16 then
+    step(seg_dpp<0x143, 0xc, DOM>(g), group >= 64); // row_bcast:31
+    return g;
+}
+
 template <int DOM>
 __device__ __forceinline__ Seg seg_readlane(const Seg &g, int lane)
 {

@@ -291,6 +291,87 @@ __global__ __launch_bounds__(256, VECIO ? 4 : 1) void heinsen_scan_rows_wave(Row
     }
 }
 
+// ---- several short rows per wave ---------------------------------------------------------------------
+//
+// Rows of at most 256 steps would leave most lanes of a wave idle.  Here a row takes `group` lanes
+// (a power of two, 8 steps per lane) and a wave takes 64 / group consecutive rows; the wave scan is
+// confined to the groups.  When the rows fill their lanes exactly (n = 8 * group) the wave's rows are
+// one contiguous span of 512 elements and move through LDS like a single long row (VECIO); otherwise
+// each lane reads and writes its own elements.
+struct PackedParams {
+    const void *a;
+    const void *b;
+    const float *x0;
+    float *out;
+    int64_t rows, n;
+    int x0_stride;
+    int group; // lanes per row
+};
+
+template <int DOM, bool LOG_IN, bool LOG_OUT, typename InT, bool VECIO>
+__global__ __launch_bounds__(256, 4) void heinsen_scan_rows_packed(PackedParams p)
+{
+    constexpr bool SIGNED = DOM == kSigned;
+    constexpr int ITEMS = 8;
+    constexpr int OW = (SIGNED && LOG_OUT) ? 2 : 1; // floats per output element
+    __shared__ u32x4 stage[VECIO ? 4 : 1][VECIO ? 64 * (ITEMS / 4 + 1) : 1];
+    const int lane = threadIdx.x & 63;
+    const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int rows_per_wave = 64 / p.group;
+    const int64_t row0 = ((int64_t)blockIdx.x * 4 + w) * rows_per_wave; // first row of this wave
+    if (row0 >= p.rows) return; // whole wave leaves together
+    const int64_t row = row0 + lane / p.group; // this lane's row (may be past the last one)
+    const bool row_ok = row < p.rows;
+    const int64_t start = (int64_t)(lane & (p.group - 1)) * ITEMS; // this lane's first step inside its row
+
+    float Av[ITEMS], Mv[ITEMS];
+    uint32_t sw, sm;
+    // elements of the wave's span that exist (VECIO: the rows are contiguous and fill their lanes)
+    const int64_t span = ((p.rows - row0 < rows_per_wave) ? (p.rows - row0) : rows_per_wave) * p.n;
+    if (VECIO) {
+        constexpr int VL = 16 / (int)sizeof(InT);
+        constexpr int NVI = ITEMS / VL;
+        const uint32_t one = sizeof(InT) == 4 ? 0x3f800000u : 0x3f803f80u;
+        const uint32_t ninf = sizeof(InT) == 4 ? 0xff800000u : 0xff80ff80u;
+        const uint32_t fa = LOG_IN ? 0u : one, fb = LOG_IN ? ninf : 0u;
+        u32x4 va[NVI], vb[NVI];
+        wave_load_blocked<NVI>(reinterpret_cast<const u32x4 *>(reinterpret_cast<const InT *>(p.a) + row0 * p.n), span / VL,
+                               u32x4{fa, fa, fa, fa}, stage[w], lane, va);
+        wave_load_blocked<NVI>(reinterpret_cast<const u32x4 *>(reinterpret_cast<const InT *>(p.b) + row0 * p.n), span / VL,
+                               u32x4{fb, fb, fb, fb}, stage[w], lane, vb);
+        unpack_inputs<InT, NVI, ITEMS>(va, Av);
+        unpack_inputs<InT, NVI, ITEMS>(vb, Mv);
+    } else {
+        const int64_t r = row_ok ? row : 0; // a lane without a row reads nothing (length 0)
+        lane_load<LOG_IN, InT, ITEMS>(reinterpret_cast<const InT *>(p.a) + r * p.n, reinterpret_cast<const InT *>(p.b) + r * p.n,
+                                      start, row_ok ? p.n : 0, Av, Mv);
+    }
+    Seg mine = lane_scan<DOM, LOG_IN, LOG_OUT, ITEMS>(Av, Mv, sw, sm);
+    const Seg incl = group_inclusive_scan<DOM>(mine, lane, p.group);
+    Seg excl = wave_shift_up<DOM>(incl);
+    if ((lane & (p.group - 1)) == 0) excl = seg_identity<DOM>(); // first lane of a row
+
+    State st;
+    encode<DOM, LOG_IN>(p.x0[(p.x0_stride && row_ok) ? row : 0], st.lx, st.s);
+    st = seg_apply<DOM>(st, excl);
+    if constexpr (VECIO && SIGNED && LOG_OUT) {
+        wave_emit_clog_blocked<ITEMS>(p.out + OW * row0 * p.n, span, stage[w], lane, st, Av, Mv, sw, sm);
+    } else if (VECIO) {
+        constexpr int NVO = ITEMS / 4;
+        const uint32_t swx = fold_state_sign<DOM>(sw, st);
+        u32x4 vo[NVO];
+#pragma unroll
+        for (int q = 0; q < NVO; ++q)
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+                vo[q][i] = f2u(emit<DOM, LOG_OUT>(st, Av[q * 4 + i], Mv[q * 4 + i], swx, q * 4 + i));
+        wave_store_blocked<NVO>(reinterpret_cast<u32x4 *>(p.out + row0 * p.n), span / 4, stage[w], lane, vo);
+    } else {
+        const int64_t r = row_ok ? row : 0;
+        lane_emit<DOM, LOG_OUT, ITEMS>(p.out + OW * r * p.n, start, row_ok ? p.n : 0, st, Av, Mv, sw, sm);
+    }
+}
+
 // ---- tiles with a chained carry ------------------------------------------------------------------------
 //
 // Tile index c inside a row is read in base 32: c = (s*32 + g)*32 + r.  Summaries are published at two
@@ -570,6 +651,7 @@ constexpr int64_t kRowsWaveMax = 64 * 32; // longest row the one-wave kernel tak
 
 struct BdnPlan {
     bool wave_kernel;
+    int group;    // > 0: several rows per wave, this many lanes per row
     int items;    // wave kernel: elements per lane
     bool vecio;
     bool multi;
@@ -590,6 +672,13 @@ BdnPlan make_plan(const ScanCall &c)
     pl.wave_kernel = c.n <= kRowsWaveMax && !(pl.rows < 64 && c.n > 512);
     if (pl.wave_kernel) {
         pl.items = c.n > 1024 ? 32 : (c.n > 512 ? 16 : 8);
+        if (c.n <= 256 && pl.rows > 1) {
+            // at least two rows fit the 64 lanes x 8 steps of a wave
+            pl.group = 1;
+            while (pl.group * 8 < c.n) pl.group *= 2;
+            // the vector path needs the rows to fill their lanes: then a wave's rows are one contiguous span
+            pl.vecio = pl.vecio && c.n == (int64_t)pl.group * 8;
+        }
         return pl;
     }
     pl.tpr = (uint32_t)ceil_div(c.n, kTile);
@@ -609,6 +698,24 @@ BdnPlan make_plan(const ScanCall &c)
 template <int DOM, bool LOG_IN, bool LOG_OUT, typename InT>
 hipError_t launch_mode(const ScanCall &c, const BdnPlan &pl, rec_t *records, LaunchTag tag)
 {
+    if (pl.wave_kernel && pl.group > 0) {
+        PackedParams p;
+        p.a = c.a;
+        p.b = c.b;
+        p.x0 = c.x0;
+        p.out = c.out;
+        p.rows = pl.rows;
+        p.n = c.n;
+        p.x0_stride = c.x0_scalar ? 0 : 1;
+        p.group = pl.group;
+        const int64_t waves = ceil_div(pl.rows, 64 / pl.group);
+        dim3 grid((unsigned)ceil_div(waves, 4)), block(256);
+        if (pl.vecio)
+            hipLaunchKernelGGL((heinsen_scan_rows_packed<DOM, LOG_IN, LOG_OUT, InT, true>), grid, block, 0, c.stream, p);
+        else
+            hipLaunchKernelGGL((heinsen_scan_rows_packed<DOM, LOG_IN, LOG_OUT, InT, false>), grid, block, 0, c.stream, p);
+        return hipGetLastError();
+    }
     if (pl.wave_kernel) {
         RowsParams p;
         p.a = c.a;
@@ -705,7 +812,9 @@ extern "C" int heinsen_debug_trace_bdn(unsigned long long *host, size_t ntiles)
 
 const char *bdn_kernel_name(const ScanCall &c)
 {
-    return make_plan(c).wave_kernel ? "heinsen_scan_rows_wave" : "heinsen_scan_tiles";
+    const BdnPlan pl = make_plan(c);
+    if (pl.wave_kernel) return pl.group > 0 ? "heinsen_scan_rows_packed" : "heinsen_scan_rows_wave";
+    return "heinsen_scan_tiles";
 }
 
 } // namespace hs
