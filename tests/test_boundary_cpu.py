@@ -73,6 +73,7 @@ def test_kernel_name_follows_layout_and_length():
     assert hb.heinsen_kernel_name(8, 1024, 4096, hb.HEINSEN_LAYOUT_BND, 0) == "heinsen_scan_bnd"
     assert hb.heinsen_kernel_name(64, 4096, 2048, hb.HEINSEN_LAYOUT_BDN, 7) == "heinsen_scan_rows_wave"
     assert hb.heinsen_kernel_name(1, 1, 1 << 26, hb.HEINSEN_LAYOUT_BDN, 8) == "heinsen_scan_tiles"
+    assert hb.heinsen_kernel_name(64, 64, 64, hb.HEINSEN_LAYOUT_BDN, 0) == "heinsen_scan_rows_packed"
     with pytest.raises(hb.HeinsenError):
         hb.heinsen_kernel_name(1, 1, 0, 0, 0)
 
