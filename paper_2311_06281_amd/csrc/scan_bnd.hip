@@ -27,7 +27,10 @@ struct BndParams {
     int x0_stride;    // 0: one x0 for all, 1: x0[b*D + d]
     int stream_out;   // 1: the output does not fit the last-level cache, write it non-temporally
     int cols_per_b;   // ceil(D / CH)
-    int ncols;        // B * cols_per_b
+    int ncols;        // B * cols_per_b; narrow rows (PACKB): ceil(B / bpack)
+    int64_t B;        // PACKB only below: batch items,
+    int dp_shift;     //   log2 of the lanes one batch item takes (the power of two >= D),
+    int bpack;        //   batch items per 64-lane column = 64 >> dp_shift
     int nchunks;      // ceil(n / (NW*T))
     uint32_t ntiles;  // ncols * nchunks
     uint32_t epoch;
@@ -97,8 +100,10 @@ __device__ __forceinline__ void unpack_signs(uint32_t s, Seg &g)
 
 // VEC channels per lane, T steps per wave, NW waves per workgroup, G tiles per group along time,
 // MINW waves per SIMD the register allocation must allow, SB: keep the scheduler from hoisting work
-// across time steps (bounds register pressure).
-template <int DOM, bool LOG_IN, bool LOG_OUT, typename InT, int VEC, int T, int NW, int G, int MINW, bool SB>
+// across time steps (bounds register pressure).  PACKB: fewer than 64 channels -- the 64 lanes of a column
+// are the channels of several batch items side by side (same tiles, carries and arithmetic; only the
+// lane -> memory mapping differs, and a wave's accesses are then pieces of D elements, one per batch item).
+template <int DOM, bool LOG_IN, bool LOG_OUT, typename InT, int VEC, int T, int NW, int G, int MINW, bool SB, bool PACKB = false>
 __global__ __launch_bounds__(NW * 64, MINW) void heinsen_scan_bnd(BndParams p)
 {
     constexpr bool SIGNED = DOM == kSigned;
@@ -137,11 +142,28 @@ __global__ __launch_bounds__(NW * 64, MINW) void heinsen_scan_bnd(BndParams p)
     const int r = chunk % G;
     const bool more = chunk + 1 < p.nchunks;
 
-    const int loff = lane * VEC; // the only per-lane part of every address
-    const int64_t d0 = (int64_t)cg * CH + loff;
-    const bool chan_ok = d0 < p.D; // D is a multiple of VEC, so the whole vector is in range
+    const int loff = lane * VEC; // the lane's place in LDS arrays and carry records
     const int64_t t0 = (int64_t)chunk * (NW * T) + (int64_t)w * T;
-    const int64_t ubase = ((int64_t)bidx * p.n + t0) * p.D + (int64_t)cg * CH; // wave-uniform
+    int moff;        // the only per-lane part of every global address (elements)
+    bool chan_ok;    // the lane has a channel
+    int64_t ubase;   // wave-uniform part of the addresses
+    int64_t x0_at;   // index of the lane's first channel in x0
+    if constexpr (PACKB) {
+        static_assert(VEC == 1, "narrow rows are mapped one channel per lane");
+        const int bb = lane >> p.dp_shift;               // batch item inside the column
+        const int d = lane & ((1 << p.dp_shift) - 1);    // channel
+        const int64_t b = (int64_t)col * p.bpack + bb;
+        chan_ok = d < p.D && b < p.B;
+        moff = bb * (int)(p.n * p.D) + d;                // the host checks that this fits 31 bits
+        ubase = ((int64_t)col * p.bpack * p.n + t0) * p.D;
+        x0_at = b * p.D + d;
+    } else {
+        const int64_t d0 = (int64_t)cg * CH + loff;
+        chan_ok = d0 < p.D; // D is a multiple of VEC, so the whole vector is in range
+        moff = loff;
+        ubase = ((int64_t)bidx * p.n + t0) * p.D + (int64_t)cg * CH;
+        x0_at = (int64_t)bidx * p.D + d0;
+    }
     const InT *ap = reinterpret_cast<const InT *>(p.a) + ubase;
     const InT *bp = reinterpret_cast<const InT *>(p.b) + ubase;
 
@@ -192,15 +214,15 @@ __global__ __launch_bounds__(NW * 64, MINW) void heinsen_scan_bnd(BndParams p)
     if (chan_ok && t0 + T <= p.n) {
 #pragma unroll
         for (int k = 0; k < T; ++k) {
-            load_vec<InT>(ap + (int64_t)k * p.D + loff, Av[k]);
-            load_vec<InT>(bp + (int64_t)k * p.D + loff, Mv[k]);
+            load_vec<InT>(ap + (int64_t)k * p.D + moff, Av[k]);
+            load_vec<InT>(bp + (int64_t)k * p.D + moff, Mv[k]);
         }
     } else {
 #pragma unroll
         for (int k = 0; k < T; ++k) {
             if (chan_ok && t0 + k < p.n) {
-                load_vec<InT>(ap + (int64_t)k * p.D + loff, Av[k]);
-                load_vec<InT>(bp + (int64_t)k * p.D + loff, Mv[k]);
+                load_vec<InT>(ap + (int64_t)k * p.D + moff, Av[k]);
+                load_vec<InT>(bp + (int64_t)k * p.D + moff, Mv[k]);
             } else {
 #pragma unroll
                 for (int v = 0; v < VEC; ++v) {
@@ -296,7 +318,7 @@ __global__ __launch_bounds__(NW * 64, MINW) void heinsen_scan_bnd(BndParams p)
         for (int v = 0; v < VEC; ++v) {
             if (g == 0) {
                 float x0v = LOG_IN ? 0.0f : 1.0f;
-                if (chan_ok) x0v = p.x0[p.x0_stride ? ((int64_t)bidx * p.D + d0 + v) : 0];
+                if (chan_ok) x0v = p.x0[p.x0_stride ? (x0_at + v) : 0];
                 encode<DOM, LOG_IN>(x0v, st[v].lx, st[v].s);
             } else {
                 st[v].lx = u2f(rec_payload(rS[v]));
@@ -351,12 +373,12 @@ __global__ __launch_bounds__(NW * 64, MINW) void heinsen_scan_bnd(BndParams p)
             float o[2 * VEC];
 #pragma unroll
             for (int v = 0; v < VEC; ++v) emit_clog(st[v], Av[k][v], Mv[k][v], swx[v], sm[v], k, o[2 * v], o[2 * v + 1]);
-            if (full || (chan_ok && t0 + k < p.n)) store_vec(op + 2 * ((int64_t)k * p.D + loff), o, p.stream_out != 0);
+            if (full || (chan_ok && t0 + k < p.n)) store_vec(op + 2 * ((int64_t)k * p.D + moff), o, p.stream_out != 0);
         } else {
             float o[VEC];
 #pragma unroll
             for (int v = 0; v < VEC; ++v) o[v] = emit<DOM, LOG_OUT>(st[v], Av[k][v], Mv[k][v], swx[v], k);
-            if (full || (chan_ok && t0 + k < p.n)) store_vec(op + (int64_t)k * p.D + loff, o, p.stream_out != 0);
+            if (full || (chan_ok && t0 + k < p.n)) store_vec(op + (int64_t)k * p.D + moff, o, p.stream_out != 0);
         }
         if (SB) __builtin_amdgcn_sched_barrier(0);
     }
@@ -374,6 +396,7 @@ constexpr int64_t kLastLevelCacheBytes = 192ll << 20;
 
 struct BndPlan {
     int vec, T, NW, G, CH, variant;
+    int dp_shift, bpack; // bpack > 1: narrow rows, the channels of bpack batch items share a 64-lane column
     int cols_per_b, ncols, nchunks, ngroups;
     uint32_t ntiles;
     size_t off_agg, off_state, records; // in records, relative to kRecordBase
@@ -435,6 +458,18 @@ BndPlan make_plan(const ScanCall &c)
     pl.CH = 64 * pl.vec;
     pl.cols_per_b = (int)ceil_div(c.D, pl.CH);
     pl.ncols = (int)(c.B * pl.cols_per_b);
+    pl.dp_shift = 6;
+    pl.bpack = 1;
+    if (c.D <= 32 && c.B > 1 && pl.variant == 0) {
+        int sh = 0;
+        while ((1 << sh) < c.D) ++sh;
+        // a lane's offset from its column's base must fit a 32-bit byte offset
+        if ((int64_t)(64 >> sh) * c.n * c.D < ((int64_t)1 << 29)) {
+            pl.dp_shift = sh;
+            pl.bpack = 64 >> sh;
+            pl.ncols = (int)ceil_div(c.B, pl.bpack);
+        }
+    }
     pl.nchunks = (int)ceil_div(c.n, (int64_t)pl.NW * pl.T);
     pl.ngroups = (int)ceil_div(pl.nchunks, pl.G);
     pl.ntiles = (uint32_t)pl.ncols * (uint32_t)pl.nchunks;
@@ -458,6 +493,9 @@ hipError_t launch_mode(const ScanCall &c, const BndPlan &pl, rec_t *records, Lau
     p.x0_stride = c.x0_scalar ? 0 : 1;
     p.stream_out = (c.B * c.D * c.n * ((SIGNED && LOG_OUT) ? 8 : 4) > kLastLevelCacheBytes) ? 1 : 0;
     p.cols_per_b = pl.cols_per_b;
+    p.B = c.B;
+    p.dp_shift = pl.dp_shift;
+    p.bpack = pl.bpack;
     p.ncols = pl.ncols;
     p.nchunks = pl.nchunks;
     p.ntiles = pl.ntiles;
@@ -489,9 +527,15 @@ hipError_t launch_mode(const ScanCall &c, const BndPlan &pl, rec_t *records, Lau
     }
 #endif
     if constexpr (SIGNED && LOG_OUT) {
-        hipLaunchKernelGGL((heinsen_scan_bnd<DOM, LOG_IN, LOG_OUT, InT, 1, 16, 16, 4, 4, true>), grid, block, 0, c.stream, p);
+        if (pl.bpack > 1)
+            hipLaunchKernelGGL((heinsen_scan_bnd<DOM, LOG_IN, LOG_OUT, InT, 1, 16, 16, 4, 4, true, true>), grid, block, 0, c.stream, p);
+        else
+            hipLaunchKernelGGL((heinsen_scan_bnd<DOM, LOG_IN, LOG_OUT, InT, 1, 16, 16, 4, 4, true>), grid, block, 0, c.stream, p);
     } else {
-        hipLaunchKernelGGL((heinsen_scan_bnd<DOM, LOG_IN, LOG_OUT, InT, 1, 32, 8, 4, 4, true>), grid, block, 0, c.stream, p);
+        if (pl.bpack > 1)
+            hipLaunchKernelGGL((heinsen_scan_bnd<DOM, LOG_IN, LOG_OUT, InT, 1, 32, 8, 4, 4, true, true>), grid, block, 0, c.stream, p);
+        else
+            hipLaunchKernelGGL((heinsen_scan_bnd<DOM, LOG_IN, LOG_OUT, InT, 1, 32, 8, 4, 4, true>), grid, block, 0, c.stream, p);
     }
     return hipGetLastError();
 }
