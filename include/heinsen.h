@@ -95,8 +95,9 @@ typedef enum {
  * different streams never share scratch; calls on one stream may come from several host threads.
  * Carries of different launches are told apart by a launch counter kept on the host, so a call that
  * is being recorded into a HIP graph (stream capture) is refused with HEINSEN_ERR_UNSUPPORTED: a
- * replay would meet its own stale carries.  Shapes that need no carries (rows of at most 2048
- * steps in the [B, D, n] layout, or any single-tile row) use no scratch and may be captured.
+ * replay would meet its own stale carries.  Shapes that need no carries (sequences of at most 2048
+ * steps in the [B, D, n] layout -- up to 16384 when B*D < 64 -- and of at most 64 steps in [B, n, D])
+ * use no scratch and may be captured.
  *
  * Data-dependent conditions are not errors and follow IEEE arithmetic: a NaN input gives NaN from
  * that step on in that sequence only; a_t = 0 restarts the sequence at b_t; b_t = 0 and x_0 = 0 are
