@@ -24,7 +24,7 @@ namespace {
 
 // ---- lane-level pieces shared by both kernels --------------------------------------------------------
 
-// Element-wise fallback for rows whose pointers or length do not allow 16-byte vectors: loads the
+// Per-lane accesses (the packed short-row kernel when its rows do not fill their lanes): loads the
 // lane's ITEMS consecutive inputs starting `start` elements into a row of length n.  Steps at or
 // beyond n are replaced by a = 1, b = 0 (which leave the state unchanged).
 template <bool LOG_IN, typename InT, int ITEMS>
@@ -161,6 +161,55 @@ __device__ __forceinline__ void wave_store_blocked_part(u32x4 *row, int64_t n_ve
     wave_lds_order();
 }
 
+// The same two moves one element at a time, for rows whose pointers or length do not allow 16-byte
+// vectors: global accesses are still coalesced (consecutive lanes, consecutive elements), the region
+// holds 32-bit slots, element c of the wave's span at slot c + c/ITEMS.  `left` elements of the row exist
+// from the wave's first one on.
+template <typename InT, int ITEMS>
+__device__ __forceinline__ void wave_load_blocked_elems(const InT *row, int64_t left, float fill, uint32_t *lds, int lane,
+                                                        float (&x)[ITEMS])
+{
+    float t[ITEMS];
+#pragma unroll
+    for (int j = 0; j < ITEMS; ++j) {
+        const int c = j * 64 + lane;
+        t[j] = (c < left) ? widen(__builtin_nontemporal_load(row + c)) : fill;
+    }
+#pragma unroll
+    for (int j = 0; j < ITEMS; ++j) {
+        const int c = j * 64 + lane;
+        lds[c + c / ITEMS] = f2u(t[j]);
+    }
+    wave_lds_order();
+#pragma unroll
+    for (int k = 0; k < ITEMS; ++k) x[k] = u2f(lds[lane * (ITEMS + 1) + k]);
+    wave_lds_order();
+}
+
+// Lanes (blocked) -> global, one float at a time; a lane owns ITEMS * PARTS consecutive floats of the
+// span and round `part` moves floats part*ITEMS .. part*ITEMS + ITEMS - 1 of every lane.
+template <int ITEMS, int PARTS>
+__device__ __forceinline__ void wave_store_blocked_elems(float *row, int64_t left, uint32_t *lds, int lane, int part,
+                                                         const float (&x)[ITEMS])
+{
+#pragma unroll
+    for (int k = 0; k < ITEMS; ++k) lds[lane * (ITEMS + 1) + k] = f2u(x[k]);
+    wave_lds_order();
+    float t[ITEMS];
+#pragma unroll
+    for (int j = 0; j < ITEMS; ++j) {
+        const int c = j * 64 + lane;
+        t[j] = u2f(lds[c + c / ITEMS]);
+    }
+#pragma unroll
+    for (int j = 0; j < ITEMS; ++j) {
+        const int c = j * 64 + lane;
+        const int gi = (c / ITEMS) * (ITEMS * PARTS) + part * ITEMS + c % ITEMS;
+        if (gi < left) __builtin_nontemporal_store(t[j], row + gi);
+    }
+    wave_lds_order();
+}
+
 template <typename InT, int NVI, int ITEMS>
 __device__ __forceinline__ void unpack_inputs(const u32x4 (&v)[NVI], float (&x)[ITEMS])
 {
@@ -233,12 +282,41 @@ __device__ __forceinline__ void wave_emit_clog_blocked(float *orow, int64_t n_el
     }
 }
 
+// Element-wise counterpart of the vector emit: `orow` points at the wave's first output element, `left`
+// elements of the row exist from there on.
+template <int DOM, bool LOG_OUT, int ITEMS>
+__device__ __forceinline__ void wave_emit_blocked_elems(float *orow, int64_t left, uint32_t *lds, int lane, const State &st,
+                                                        const float (&Av)[ITEMS], const float (&Mv)[ITEMS], uint32_t sw,
+                                                        uint32_t sm)
+{
+    constexpr bool SIGNED = DOM == kSigned;
+    const uint32_t swx = fold_state_sign<DOM>(sw, st);
+    left = left < 0 ? 0 : left;
+    if constexpr (SIGNED && LOG_OUT) {
+#pragma unroll
+        for (int part = 0; part < 2; ++part) {
+            float o[ITEMS];
+#pragma unroll
+            for (int i = 0; i < ITEMS / 2; ++i) {
+                const int k = part * (ITEMS / 2) + i;
+                emit_clog(st, Av[k], Mv[k], swx, sm, k, o[2 * i], o[2 * i + 1]);
+            }
+            wave_store_blocked_elems<ITEMS, 2>(orow, 2 * left, lds, lane, part, o);
+        }
+    } else {
+        float o[ITEMS];
+#pragma unroll
+        for (int k = 0; k < ITEMS; ++k) o[k] = emit<DOM, LOG_OUT>(st, Av[k], Mv[k], swx, k);
+        wave_store_blocked_elems<ITEMS, 1>(orow, left, lds, lane, 0, o);
+    }
+}
+
 template <int DOM, bool LOG_IN, bool LOG_OUT, typename InT, int ITEMS, bool VECIO>
 __global__ __launch_bounds__(256, VECIO ? 4 : 1) void heinsen_scan_rows_wave(RowsParams p)
 {
     constexpr bool SIGNED = DOM == kSigned;
     // 16-byte slots per wave: the output row (ITEMS/4 vectors per lane, the larger of the two) plus padding
-    __shared__ u32x4 stage[VECIO ? 4 : 1][VECIO ? 64 * (ITEMS / 4 + 1) : 1];
+    __shared__ u32x4 stage[4][64 * (ITEMS / 4 + 1)];
     const int lane = threadIdx.x & 63;
     const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int64_t row = (int64_t)blockIdx.x * 4 + w;
@@ -247,7 +325,6 @@ __global__ __launch_bounds__(256, VECIO ? 4 : 1) void heinsen_scan_rows_wave(Row
     const InT *brow = reinterpret_cast<const InT *>(p.b) + row * p.n;
     constexpr int OW = (SIGNED && LOG_OUT) ? 2 : 1; // floats per output element
     float *orow = p.out + OW * row * p.n;
-    const int64_t start = (int64_t)lane * ITEMS;
 
     float Av[ITEMS], Mv[ITEMS];
     uint32_t sw, sm;
@@ -266,7 +343,9 @@ __global__ __launch_bounds__(256, VECIO ? 4 : 1) void heinsen_scan_rows_wave(Row
         unpack_inputs<InT, NVI, ITEMS>(va, Av);
         unpack_inputs<InT, NVI, ITEMS>(vb, Mv);
     } else {
-        lane_load<LOG_IN, InT, ITEMS>(arow, brow, start, p.n, Av, Mv);
+        uint32_t *slots = reinterpret_cast<uint32_t *>(stage[w]);
+        wave_load_blocked_elems<InT, ITEMS>(arow, p.n, LOG_IN ? 0.0f : 1.0f, slots, lane, Av);
+        wave_load_blocked_elems<InT, ITEMS>(brow, p.n, LOG_IN ? -INFINITY : 0.0f, slots, lane, Mv);
     }
     Seg mine = lane_scan<DOM, LOG_IN, LOG_OUT, ITEMS>(Av, Mv, sw, sm);
     Seg excl = wave_shift_up<DOM>(wave_inclusive_scan<DOM>(mine));
@@ -287,7 +366,7 @@ __global__ __launch_bounds__(256, VECIO ? 4 : 1) void heinsen_scan_rows_wave(Row
                 vo[q][i] = f2u(emit<DOM, LOG_OUT>(st, Av[q * 4 + i], Mv[q * 4 + i], swx, q * 4 + i));
         wave_store_blocked<NVO>(reinterpret_cast<u32x4 *>(orow), p.n / 4, stage[w], lane, vo);
     } else {
-        lane_emit<DOM, LOG_OUT, ITEMS>(orow, start, p.n, st, Av, Mv, sw, sm);
+        wave_emit_blocked_elems<DOM, LOG_OUT, ITEMS>(orow, p.n, reinterpret_cast<uint32_t *>(stage[w]), lane, st, Av, Mv, sw, sm);
     }
 }
 
@@ -479,7 +558,6 @@ __global__ __launch_bounds__(kTileWaves * 64) void heinsen_scan_tiles(TileParams
     const uint32_t c = tile % p.tpr;
     const InT *arow = reinterpret_cast<const InT *>(p.a) + row * p.n;
     const InT *brow = reinterpret_cast<const InT *>(p.b) + row * p.n;
-    const int64_t start = (int64_t)c * kTile + (int64_t)threadIdx.x * ITEMS;
 
     // ---- wave 0 asks for the carry records it needs before the tile's own loads (see scan_bnd.hip) ---
     const uint32_t r = c & 31u, g = (c >> 5) & 31u, sb = c >> 10;
@@ -510,7 +588,7 @@ __global__ __launch_bounds__(kTileWaves * 64) void heinsen_scan_tiles(TileParams
 
     // global <-> lane traffic of each wave goes through its own LDS region (coalesced both ways); the pad
     // slot after the last lane is never used, and leaving it out lets four workgroups share a CU
-    __shared__ u32x4 stage[VECIO ? NW : 1][VECIO ? 64 * (ITEMS / 4 + 1) - 1 : 1];
+    __shared__ u32x4 stage[NW][64 * (ITEMS / 4 + 1) - (VECIO ? 1 : 0)];
     const int64_t wstart = (int64_t)c * kTile + (int64_t)w * (64 * ITEMS); // first element of this wave
     float Av[ITEMS], Mv[ITEMS];
     uint32_t sw, sm;
@@ -528,7 +606,9 @@ __global__ __launch_bounds__(kTileWaves * 64) void heinsen_scan_tiles(TileParams
         unpack_inputs<InT, NVI, ITEMS>(va, Av);
         unpack_inputs<InT, NVI, ITEMS>(vb, Mv);
     } else {
-        lane_load<LOG_IN, InT, ITEMS>(arow, brow, start, p.n, Av, Mv);
+        uint32_t *slots = reinterpret_cast<uint32_t *>(stage[w]);
+        wave_load_blocked_elems<InT, ITEMS>(arow + wstart, p.n - wstart, LOG_IN ? 0.0f : 1.0f, slots, lane, Av);
+        wave_load_blocked_elems<InT, ITEMS>(brow + wstart, p.n - wstart, LOG_IN ? -INFINITY : 0.0f, slots, lane, Mv);
     }
     Seg mine = lane_scan<DOM, LOG_IN, LOG_OUT, ITEMS>(Av, Mv, sw, sm);
     Seg incl = wave_inclusive_scan<DOM>(mine);
@@ -639,7 +719,8 @@ __global__ __launch_bounds__(kTileWaves * 64) void heinsen_scan_tiles(TileParams
         n_vec = n_vec < 0 ? 0 : n_vec;
         wave_store_blocked<NVO>(reinterpret_cast<u32x4 *>(orow + wstart), n_vec, stage[w], lane, vo);
     } else {
-        lane_emit<DOM, LOG_OUT, ITEMS>(orow, start, p.n, st, Av, Mv, sw, sm);
+        wave_emit_blocked_elems<DOM, LOG_OUT, ITEMS>(orow + OW * wstart, p.n - wstart, reinterpret_cast<uint32_t *>(stage[w]), lane,
+                                                     st, Av, Mv, sw, sm);
     }
     HS_STAMP(6);
     HS_STAMP(7);
