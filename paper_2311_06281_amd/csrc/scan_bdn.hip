@@ -24,27 +24,6 @@ namespace {
 
 // ---- lane-level pieces shared by both kernels --------------------------------------------------------
 
-// Per-lane accesses (the packed short-row kernel when its rows do not fill their lanes): loads the
-// lane's ITEMS consecutive inputs starting `start` elements into a row of length n.  Steps at or
-// beyond n are replaced by a = 1, b = 0 (which leave the state unchanged).
-template <bool LOG_IN, typename InT, int ITEMS>
-__device__ __forceinline__ void lane_load(const InT *arow, const InT *brow, int64_t start, int64_t n,
-                                          float (&Av)[ITEMS], float (&Mv)[ITEMS])
-{
-    const float id_a = LOG_IN ? 0.0f : 1.0f;
-    const float id_b = LOG_IN ? -INFINITY : 0.0f;
-#pragma unroll
-    for (int k = 0; k < ITEMS; ++k) {
-        if (start + k < n) {
-            Av[k] = widen(arow[start + k]);
-            Mv[k] = widen(brow[start + k]);
-        } else {
-            Av[k] = id_a;
-            Mv[k] = id_b;
-        }
-    }
-}
-
 // Encodes and scans the lane's elements serially.  On return Av[k], Mv[k] and bit k of sw (and of sm)
 // hold the per-element records (see stash); the summary of all ITEMS steps is returned.
 template <int DOM, bool LOG_IN, bool LOG_OUT, int ITEMS>
@@ -230,29 +209,6 @@ __device__ __forceinline__ void unpack_inputs(const u32x4 (&v)[NVI], float (&x)[
 }
 
 
-// Element-wise fallback: emits the lane's elements given the state at the lane's first step.
-template <int DOM, bool LOG_OUT, int ITEMS>
-__device__ __forceinline__ void lane_emit(float *orow, int64_t start, int64_t n, const State &st,
-                                          const float (&Av)[ITEMS], const float (&Mv)[ITEMS], uint32_t sw, uint32_t sm)
-{
-    constexpr bool SIGNED = DOM == kSigned;
-    const uint32_t swx = fold_state_sign<DOM>(sw, st);
-#pragma unroll
-    for (int k = 0; k < ITEMS; ++k) {
-        if constexpr (SIGNED && LOG_OUT) {
-            float re, im;
-            emit_clog(st, Av[k], Mv[k], swx, sm, k, re, im);
-            if (start + k < n) {
-                orow[2 * (start + k)] = re;
-                orow[2 * (start + k) + 1] = im;
-            }
-        } else {
-            const float o = emit<DOM, LOG_OUT>(st, Av[k], Mv[k], swx, k);
-            if (start + k < n) orow[start + k] = o;
-        }
-    }
-}
-
 // Complex output (log output on a signed domain), vector path: emits the lane's elements and writes them,
 // coalesced, through the wave's LDS region.  `orow` points at the wave's first output element, n_elems
 // elements of the row are left from there (a multiple of four).  The output has twice the bytes of a real
@@ -376,7 +332,7 @@ __global__ __launch_bounds__(256, VECIO ? 4 : 1) void heinsen_scan_rows_wave(Row
 // (a power of two, 8 steps per lane) and a wave takes 64 / group consecutive rows; the wave scan is
 // confined to the groups.  When the rows fill their lanes exactly (n = 8 * group) the wave's rows are
 // one contiguous span of 512 elements and move through LDS like a single long row (VECIO); otherwise
-// each lane reads and writes its own elements.
+// the span is still read and written coalesced, one element at a time, and sorted into the lanes' slots.
 struct PackedParams {
     const void *a;
     const void *b;
@@ -393,7 +349,7 @@ __global__ __launch_bounds__(256, 4) void heinsen_scan_rows_packed(PackedParams 
     constexpr bool SIGNED = DOM == kSigned;
     constexpr int ITEMS = 8;
     constexpr int OW = (SIGNED && LOG_OUT) ? 2 : 1; // floats per output element
-    __shared__ u32x4 stage[VECIO ? 4 : 1][VECIO ? 64 * (ITEMS / 4 + 1) : 1];
+    __shared__ u32x4 stage[4][64 * (ITEMS / 4 + 1)];
     const int lane = threadIdx.x & 63;
     const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int rows_per_wave = 64 / p.group;
@@ -407,6 +363,14 @@ __global__ __launch_bounds__(256, 4) void heinsen_scan_rows_packed(PackedParams 
     uint32_t sw, sm;
     // elements of the wave's span that exist (VECIO: the rows are contiguous and fill their lanes)
     const int64_t span = ((p.rows - row0 < rows_per_wave) ? (p.rows - row0) : rows_per_wave) * p.n;
+    // slot of element c of the span when rows do not fill their lanes; c / n through a reciprocal: c + 1/2
+    // over n is at least 1/(2n) >= 1/512 away from every integer, far more than the rounding of the product
+    const float inv_n = 1.0f / (float)p.n;
+    auto span_slot = [&](int c) -> int {
+        const int r = (int)(((float)c + 0.5f) * inv_n);
+        const int s_ = c - r * (int)p.n;
+        return (r * p.group + (s_ >> 3)) * (ITEMS + 1) + (s_ & 7);
+    };
     if (VECIO) {
         constexpr int VL = 16 / (int)sizeof(InT);
         constexpr int NVI = ITEMS / VL;
@@ -421,9 +385,29 @@ __global__ __launch_bounds__(256, 4) void heinsen_scan_rows_packed(PackedParams 
         unpack_inputs<InT, NVI, ITEMS>(va, Av);
         unpack_inputs<InT, NVI, ITEMS>(vb, Mv);
     } else {
-        const int64_t r = row_ok ? row : 0; // a lane without a row reads nothing (length 0)
-        lane_load<LOG_IN, InT, ITEMS>(reinterpret_cast<const InT *>(p.a) + r * p.n, reinterpret_cast<const InT *>(p.b) + r * p.n,
-                                      start, row_ok ? p.n : 0, Av, Mv);
+        // The wave's rows are still one contiguous span of memory, but a row does not fill its lanes: read
+        // the span coalesced, one element per lane and round, and drop element c = (row r, step s) into
+        // the slot of the lane that owns it, (r * group + s / 8) * 9 + s % 8.
+        uint32_t *slots = reinterpret_cast<uint32_t *>(stage[w]);
+        auto gather = [&](const InT *src, float fill, float (&x)[ITEMS]) {
+            float t[ITEMS];
+#pragma unroll
+            for (int j = 0; j < ITEMS; ++j) {
+                const int c = j * 64 + lane;
+                t[j] = (c < span) ? widen(__builtin_nontemporal_load(src + c)) : fill;
+            }
+#pragma unroll
+            for (int j = 0; j < ITEMS; ++j) {
+                const int c = j * 64 + lane;
+                if (c < span) slots[span_slot(c)] = f2u(t[j]);
+            }
+            wave_lds_order();
+#pragma unroll
+            for (int k = 0; k < ITEMS; ++k) x[k] = (row_ok && start + k < p.n) ? u2f(slots[lane * (ITEMS + 1) + k]) : fill;
+            wave_lds_order();
+        };
+        gather(reinterpret_cast<const InT *>(p.a) + row0 * p.n, LOG_IN ? 0.0f : 1.0f, Av);
+        gather(reinterpret_cast<const InT *>(p.b) + row0 * p.n, LOG_IN ? -INFINITY : 0.0f, Mv);
     }
     Seg mine = lane_scan<DOM, LOG_IN, LOG_OUT, ITEMS>(Av, Mv, sw, sm);
     const Seg incl = group_inclusive_scan<DOM>(mine, lane, p.group);
@@ -446,8 +430,33 @@ __global__ __launch_bounds__(256, 4) void heinsen_scan_rows_packed(PackedParams 
                 vo[q][i] = f2u(emit<DOM, LOG_OUT>(st, Av[q * 4 + i], Mv[q * 4 + i], swx, q * 4 + i));
         wave_store_blocked<NVO>(reinterpret_cast<u32x4 *>(p.out + row0 * p.n), span / 4, stage[w], lane, vo);
     } else {
-        const int64_t r = row_ok ? row : 0;
-        lane_emit<DOM, LOG_OUT, ITEMS>(p.out + OW * r * p.n, start, row_ok ? p.n : 0, st, Av, Mv, sw, sm);
+        // the reverse move: lanes drop their results into their slots, the span is written coalesced
+        // (a complex output in two rounds, real parts then imaginary parts)
+        uint32_t *slots = reinterpret_cast<uint32_t *>(stage[w]);
+        const uint32_t swx = fold_state_sign<DOM>(sw, st);
+        float *dst = p.out + OW * row0 * p.n;
+#pragma unroll
+        for (int part = 0; part < OW; ++part) {
+#pragma unroll
+            for (int k2 = 0; k2 < ITEMS; ++k2) {
+                float o;
+                if constexpr (SIGNED && LOG_OUT) {
+                    float re, im;
+                    emit_clog(st, Av[k2], Mv[k2], swx, sm, k2, re, im);
+                    o = part == 0 ? re : im;
+                } else {
+                    o = emit<DOM, LOG_OUT>(st, Av[k2], Mv[k2], swx, k2);
+                }
+                slots[lane * (ITEMS + 1) + k2] = f2u(o);
+            }
+            wave_lds_order();
+#pragma unroll
+            for (int j = 0; j < ITEMS; ++j) {
+                const int c = j * 64 + lane;
+                if (c < span) __builtin_nontemporal_store(u2f(slots[span_slot(c)]), dst + OW * c + part);
+            }
+            wave_lds_order();
+        }
     }
 }
 
