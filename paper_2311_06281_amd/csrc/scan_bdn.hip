@@ -1,10 +1,12 @@
 // Sequence-contiguous path: a, b, out are [rows, n] with rows = B*D; time runs along the lanes.
 //
-// Two kernels.
+// Three kernels.
 //  * rows_wave: one wave per row for rows that fit 64*ITEMS elements.  Lane i owns ITEMS consecutive
 //    steps, scans them serially, the 64 lane summaries are scanned with DPP, each lane derives the
 //    state at its first step and emits its elements.  No barrier, no global scratch; LDS only as the
 //    wave's private staging area for coalesced global accesses.
+//  * rows_packed: rows of at most 256 steps, several per wave; the wave scan is confined to the lanes
+//    of a row.
 //  * tiles: rows longer than that are cut into tiles of NW*64*ITEMS elements, one workgroup per
 //    tile: the same lane and wave scans, wave summaries chained through LDS, tile summaries chained
 //    through global memory in a two-level tree (see below); folds happen in a fixed order, so results
@@ -22,7 +24,7 @@ extern unsigned long long *g_trace_bdn_storage;
 #endif
 namespace {
 
-// ---- lane-level pieces shared by both kernels --------------------------------------------------------
+// ---- lane-level pieces shared by the kernels ----------------------------------------------------------
 
 // Encodes and scans the lane's elements serially.  On return Av[k], Mv[k] and bit k of sw (and of sm)
 // hold the per-element records (see stash); the summary of all ITEMS steps is returned.
