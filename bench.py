@@ -240,6 +240,8 @@ def main() -> int:
                      "kernel": kernel, "kernel_ms_mean": kern_ms, "kernel_ms_median": kern_med,
                      "kernel_ms_min": kern_min, "algorithmic_bytes": alg_bytes},
     }
+    props = torch.cuda.get_device_properties(0)
+    result["device"] = {"name": props.name, "arch": getattr(props, "gcnArchName", None), "compute_units": props.multi_processor_count}
     if not args.no_others:
         others = []
         for idx in (1, 3, 4, 5):
