@@ -52,7 +52,9 @@ def _assert_signed(got, ref, layout):
     assert np.all(np.abs(got - ref) <= bound + 1e-30), float(np.max(np.abs(got - ref) / (bound + 1e-30)))
 
 
-SHAPES = [("BDN", (2, 3, 700)), ("BDN", (1, 2, 9000)), ("BDN", (1, 1, 50000)), ("BND", (2, 900, 70)), ("BND", (1, 300, 130))]
+SHAPES = [("BDN", (2, 3, 700)), ("BDN", (1, 2, 9000)), ("BDN", (1, 1, 50000)), ("BND", (2, 900, 70)), ("BND", (1, 300, 130)),
+          # several rows per wave (rows filling their lanes, and not), narrow channels, short sequences
+          ("BDN", (4, 8, 64)), ("BDN", (2, 5, 100)), ("BND", (9, 300, 8)), ("BND", (3, 40, 70))]
 
 
 @pytest.mark.parametrize("layout,shape", SHAPES)
@@ -63,7 +65,10 @@ def test_zero_coefficients_restart_the_sequence(gpu, layout, shape):
     taxis = 1 if layout == "BND" else 2
     # a_t = 0 at scattered steps (also at the first step and in runs): x_t = b_t there
     idx = [slice(None)] * 3
-    for t in (0, 5, 6, 7, 63, 64, shape[taxis] // 2, shape[taxis] - 1):
+    nsteps = shape[taxis]
+    for t in (0, 5, 6, 7, 63, 64, nsteps // 2, nsteps - 1):
+        if t >= nsteps:
+            continue
         idx[taxis] = t
         a[tuple(idx)] = 0.0
     B = shape[0]
@@ -74,6 +79,8 @@ def test_zero_coefficients_restart_the_sequence(gpu, layout, shape):
     assert np.isfinite(got).all()
     _assert_signed(got, ref, layout)
     for t in (0, 6, 64):
+        if t >= nsteps:
+            continue
         idx[taxis] = t
         np.testing.assert_allclose(got[tuple(idx)], b[tuple(idx)], rtol=1e-5, atol=1e-6)
 
@@ -280,7 +287,8 @@ def test_log_inputs_accept_minus_infinity_as_zero(gpu):
 
 def test_scalar_x0_broadcasts(gpu):
     rng = np.random.default_rng(7)
-    for layout, shape in (("BDN", (2, 5, 900)), ("BND", (2, 400, 70))):
+    for layout, shape in (("BDN", (2, 5, 900)), ("BND", (2, 400, 70)), ("BDN", (6, 7, 32)), ("BDN", (2, 9, 50)), ("BND", (20, 300, 4)),
+                          ("BND", (2, 30, 100))):
         a = rng.uniform(-1, 1, shape).astype(np.float32)
         b = rng.normal(0, 1, shape).astype(np.float32)
         B = shape[0]
