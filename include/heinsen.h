@@ -81,7 +81,8 @@ typedef enum {
  *                            May be exactly a_or_log_a or b_or_log_b when those are float32 (every tile
  *                            reads its inputs before it writes; "in situ", Sec. 1); any other overlap
  *                            is undefined.
- *   B, D, n                : batch, channels, sequence length; all >= 1 and B*D*n < 2^62.
+ *   B, D, n                : batch, channels, sequence length; all >= 1 and B*D*n < 2^62 (beyond 2^42
+ *                            elements the call is refused as unsupported: tile counters are 32-bit).
  *   layout                 : a heinsen_layout_t value.
  *   flags                  : OR of the flag bits above.
  *   stream                 : a hipStream_t (NULL = the default stream).
@@ -95,9 +96,8 @@ typedef enum {
  * different streams never share scratch; calls on one stream may come from several host threads.
  * Carries of different launches are told apart by a launch counter kept on the host, so a call that
  * is being recorded into a HIP graph (stream capture) is refused with HEINSEN_ERR_UNSUPPORTED: a
- * replay would meet its own stale carries.  Shapes that need no carries (sequences of at most 2048
- * steps in the [B, D, n] layout -- up to 16384 when B*D < 64 -- and of at most 64 steps in [B, n, D])
- * use no scratch and may be captured.
+ * replay would meet its own stale carries.  Shapes that need no carries (sequences of at most 16384
+ * steps in the [B, D, n] layout and of at most 64 steps in [B, n, D]) use no scratch and may be captured.
  *
  * Data-dependent conditions are not errors and follow IEEE arithmetic: a NaN input gives NaN from
  * that step on in that sequence only; a_t = 0 restarts the sequence at b_t; b_t = 0 and x_0 = 0 are
