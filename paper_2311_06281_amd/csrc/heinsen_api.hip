@@ -160,7 +160,7 @@ const char *heinsen_status_string(int status)
 
 int heinsen_last_hip_error(void) { return t_last_hip_error; }
 
-int heinsen_version(void) { return 100; /* 0.1.0 */ }
+int heinsen_version(void) { return 200; /* 0.2.0: OUT_COMPLEX, LINEAR */ }
 
 int heinsen_release_scratch(void)
 {
