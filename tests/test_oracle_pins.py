@@ -293,6 +293,33 @@ def test_scaled_complex_log_matches_plain_one_in_range_and_closed_form_beyond():
     np.testing.assert_array_equal(z.imag, [np.pi, np.pi])
 
 
+def test_superposition_and_time_shift():
+    """For fixed a the recurrence is linear in (b, x_0): x(a, b1 + b2, u + v) = x(a, b1, u) + x(a, b2, v), and
+    scaling (b, x_0) scales x; a sequence restarted from its own state x_k continues itself.  None of these
+    mentions the closed form, so a wrong index, a dropped term or a swapped operand in the oracle breaks them."""
+    rng = np.random.default_rng(17)
+    n = 300
+    a = rng.uniform(-1.2, 1.2, n)
+    b1, b2 = rng.normal(0, 1, n), rng.normal(0, 3, n)
+    u, v = 0.7, -2.5
+    x12 = oracle.seq_f64(a, b1 + b2, u + v)
+    x1 = oracle.seq_f64(a, b1, u)
+    x2 = oracle.seq_f64(a, b2, v)
+    scale = np.maximum.accumulate(np.abs(x1) + np.abs(x2)) + 1.0
+    assert np.all(np.abs(x12 - (x1 + x2)) <= 1e-13 * scale)
+    assert np.all(np.abs(oracle.seq_f64(a, -3.0 * b1, -3.0 * u) + 3.0 * x1) <= 1e-13 * scale)
+    # impulse response: b = 0 except b_k = 1, x_0 = 0  =>  x_t = prod_{k < s <= t} a_s for t >= k, 0 before
+    k = 41
+    e = np.zeros(n)
+    e[k] = 1.0
+    h = oracle.seq_f64(a, e, 0.0)
+    assert np.all(h[:k] == 0.0) and h[k] == 1.0
+    np.testing.assert_allclose(h[k + 1:k + 40], np.cumprod(a[k + 1:k + 40]), rtol=1e-13)
+    # restart: the tail computed from x_k equals the tail of the whole
+    k = 123
+    np.testing.assert_array_equal(oracle.seq_f64(a[k:], b1[k:], x1[k - 1]), x1[k:])
+
+
 def test_log_domain_definition_matches_linear_definition():
     cfg = workloads.CONFIGS[4].scaled(B=2, D=4, n=256)
     batch = workloads.generate(cfg)
