@@ -55,6 +55,7 @@ P = 4096  # a non-null, aligned fake address: validation must fail before it is 
     ((P, P, P, P, 1, 1, 8, 2, 0), hb.HEINSEN_ERR_INVALID_ARG),          # unknown layout
     ((P, P, P, P, 1, 1, 8, 0, 1 << 9), hb.HEINSEN_ERR_INVALID_ARG),     # unknown flag bit
     ((P, P, P, P, 1 << 31, 1 << 31, 1 << 10, 0, 0), hb.HEINSEN_ERR_INVALID_ARG),  # B*D*n overflow
+    ((P, P, P, P, 1, 1, 1 << 42, 1, 0), hb.HEINSEN_ERR_UNSUPPORTED),    # more elements than 32-bit tile counters cover
     ((P + 2, P, P, P, 1, 1, 8, 0, 0), hb.HEINSEN_ERR_INVALID_ARG),      # misaligned float32 input
     ((P + 1, P, P, P, 1, 1, 8, 0, hb.HEINSEN_IN_BF16), hb.HEINSEN_ERR_INVALID_ARG),  # misaligned bf16 input
     ((P, P, P, P + 2, 1, 1, 8, 0, 0), hb.HEINSEN_ERR_INVALID_ARG),      # misaligned out
