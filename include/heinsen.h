@@ -64,7 +64,7 @@ typedef enum {
                                     LOG_OUTPUT, LINEAR with a log-domain flag)                           */
     HEINSEN_ERR_UNSUPPORTED = 2, /* a legal but unimplemented combination: LOG_OUTPUT on a signed domain
                                     without OUT_COMPLEX, OUT_COMPLEX with LOG_INPUTS, a call that needs
-                                    scratch while its stream is being captured                         */
+                                    scratch recorded into a graph on a stream that has none yet         */
     HEINSEN_ERR_ALLOC = 3,       /* scratch memory could not be allocated; nothing was launched          */
     HEINSEN_ERR_HIP = 4          /* a HIP runtime call failed; see heinsen_last_hip_error()              */
 } heinsen_status_t;
@@ -94,10 +94,18 @@ typedef enum {
  * with hipMalloc on the first call that needs it or needs more (that call synchronises the stream
  * if it replaces a buffer); later calls of the same or smaller shape allocate nothing.  Calls on
  * different streams never share scratch; calls on one stream may come from several host threads.
- * Carries of different launches are told apart by a launch counter kept on the host, so a call that
- * is being recorded into a HIP graph (stream capture) is refused with HEINSEN_ERR_UNSUPPORTED: a
- * replay would meet its own stale carries.  Shapes that need no carries (sequences of at most 16384
- * steps in the [B, D, n] layout and of at most 64 steps in [B, n, D]) use no scratch and may be captured.
+ * Carries of different launches are told apart by a launch counter.  For an ordinary call the host
+ * keeps it.  A call that is being recorded into a HIP graph (stream capture) is replayed with the same
+ * arguments many times and may not allocate: it uses the scratch its stream already has -- make one
+ * ordinary call of at least the same shape on that stream first, as a warm-up does -- and records a
+ * one-workgroup kernel in front of the scan that renews the counter in the scratch at every replay.
+ * Without such scratch the call is refused with HEINSEN_ERR_UNSUPPORTED and nothing is recorded.
+ * A graph keeps using the scratch it was recorded with (a later, larger ordinary call gets a new
+ * buffer and the old one lives on until heinsen_release_scratch): its replays must not overlap with
+ * one another or with ordinary calls on the stream it was recorded on, and heinsen_release_scratch
+ * must not be called while the graph may still be replayed.  Shapes that need no carries (sequences
+ * of at most 16384 steps in the [B, D, n] layout and of at most 64 steps in [B, n, D]) use no scratch
+ * and may be captured without any of this.
  *
  * Data-dependent conditions are not errors and follow IEEE arithmetic: a NaN input gives NaN from
  * that step on in that sequence only; a_t = 0 restarts the sequence at b_t; b_t = 0 and x_0 = 0 are

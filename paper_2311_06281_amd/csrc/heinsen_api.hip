@@ -7,6 +7,7 @@
 #include <map>
 #include <mutex>
 #include <utility>
+#include <vector>
 
 namespace {
 
@@ -20,9 +21,33 @@ thread_local int t_last_hip_error = 0;
 struct Scratch {
     unsigned long long *records = nullptr;
     size_t capacity = 0;      // in records, including the header
-    uint32_t epoch = 0;       // epoch of the last launch (0: none yet)
-    uint32_t ticket_base = 0; // value of the ticket counter when the next launch starts
+    uint32_t epoch = 0;       // epoch of the last ordinary launch (even; 0: none yet)
+    uint32_t ticket_base = 0; // value of the ticket counter when the next ordinary launch starts
+    bool in_graph = false;    // a captured launch holds this buffer's address: it is not freed on growth
+    std::vector<unsigned long long *> retired; // such buffers, replaced by larger ones; freed on release
 };
+
+// Recorded in front of every captured launch (one workgroup): gives the replay a fresh odd epoch and a
+// ticket counter at zero.  When the 30-bit epoch comes round, the records are cleared so that no tag of
+// an earlier cycle can match.
+__global__ void heinsen_graph_prologue(unsigned long long *records, size_t capacity)
+{
+    __shared__ uint32_t s_next, s_wrap;
+    if (threadIdx.x == 0) {
+        const uint32_t e = (uint32_t)records[hs::kHeaderGraphEpoch];
+        const uint32_t ne = e == 0 ? 1u : e + 2u;
+        s_wrap = ne >= (1u << 30) ? 1u : 0u;
+        s_next = s_wrap ? 1u : ne;
+    }
+    __syncthreads();
+    if (s_wrap)
+        for (size_t i = hs::kRecordBase + threadIdx.x; i < capacity; i += blockDim.x) records[i] = 0;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        records[hs::kHeaderGraphTicket] = 0;
+        records[hs::kHeaderGraphEpoch] = s_next;
+    }
+}
 
 std::mutex g_mutex;
 std::map<std::pair<int, hipStream_t>, Scratch> g_scratch;
@@ -78,14 +103,18 @@ int prepare_launch(hipStream_t stream, const hs::ScratchNeed &need, Scratch *&ou
     if (!hip_ok(hipGetDevice(&dev))) return HEINSEN_ERR_HIP;
     Scratch &s = g_scratch[std::make_pair(dev, stream)];
     const size_t want = hs::kRecordBase + need.records;
-    const bool wrap = s.epoch >= 0x3ffffffeu; // 30-bit epochs: start over on a cleared buffer
+    const bool wrap = s.epoch >= 0x3ffffffcu; // 30-bit epochs: start over on a cleared buffer
     if (s.capacity < want || wrap) {
         // work queued on the old buffer must drain before it is replaced or cleared
         if (s.records && !hip_ok(hipStreamSynchronize(stream))) return HEINSEN_ERR_HIP;
         if (s.capacity < want) {
-            if (s.records) (void)hipFree(s.records);
+            if (s.records) {
+                if (s.in_graph) s.retired.push_back(s.records); // a graph may still replay into it
+                else (void)hipFree(s.records);
+            }
             s.records = nullptr;
             s.capacity = 0;
+            s.in_graph = false;
             const size_t cap = hs::align_up(want + want / 2, 512);
             void *ptr = nullptr;
             if (!hip_ok(hipMalloc(&ptr, cap * sizeof(unsigned long long)))) return HEINSEN_ERR_ALLOC;
@@ -96,9 +125,10 @@ int prepare_launch(hipStream_t stream, const hs::ScratchNeed &need, Scratch *&ou
         s.epoch = 0;
         s.ticket_base = 0;
     }
-    s.epoch += 1;
+    s.epoch += 2; // even: launches replayed from graphs use the odd ones
     tag.epoch = s.epoch;
     tag.ticket_base = s.ticket_base;
+    tag.from_header = false;
     s.ticket_base += need.tickets; // wraps modulo 2^32 together with the device counter
     out = &s;
     return HEINSEN_OK;
@@ -128,17 +158,32 @@ int heinsen_scan(const void *a, const void *b, const void *x0, void *out, int64_
 
     const hs::ScratchNeed need = bnd ? hs::bnd_scratch(c) : hs::bdn_scratch(c);
     if (need.records == 0 && need.tickets == 0) {
-        hipError_t e = bnd ? hs::bnd_launch(c, nullptr, hs::LaunchTag{0, 0}) : hs::bdn_launch(c, nullptr, hs::LaunchTag{0, 0});
+        hipError_t e = bnd ? hs::bnd_launch(c, nullptr, hs::LaunchTag{0, 0, false}) : hs::bdn_launch(c, nullptr, hs::LaunchTag{0, 0, false});
         return hip_ok(e) ? HEINSEN_OK : HEINSEN_ERR_HIP;
     }
-    // The carry records are told apart by a per-launch epoch that the host hands out, so a launch that
-    // is recorded once and replayed many times (HIP graph capture) would see its own stale records.
+    // The carry records are told apart by a per-launch epoch.  An ordinary launch gets it from the host;
+    // a launch that is recorded once and replayed many times (HIP graph capture) cannot, and nothing may
+    // be allocated while a stream is capturing: such a call uses the scratch the stream already has (an
+    // earlier ordinary call of at least this size made it) and takes epoch and tickets from its header,
+    // which a small kernel recorded in front of it renews at every replay.
     hipStreamCaptureStatus cap = hipStreamCaptureStatusNone;
-    if (c.stream != nullptr && hipStreamIsCapturing(c.stream, &cap) == hipSuccess && cap != hipStreamCaptureStatusNone)
-        return HEINSEN_ERR_UNSUPPORTED;
+    if (c.stream != nullptr && hipStreamIsCapturing(c.stream, &cap) == hipSuccess && cap != hipStreamCaptureStatusNone) {
+        std::lock_guard<std::mutex> lock(g_mutex);
+        int dev = 0;
+        if (!hip_ok(hipGetDevice(&dev))) return HEINSEN_ERR_HIP;
+        auto it = g_scratch.find(std::make_pair(dev, c.stream));
+        if (it == g_scratch.end() || it->second.capacity < hs::kRecordBase + need.records) return HEINSEN_ERR_UNSUPPORTED;
+        Scratch &sc = it->second;
+        sc.in_graph = true;
+        hipLaunchKernelGGL(heinsen_graph_prologue, dim3(1), dim3(256), 0, c.stream, sc.records, sc.capacity);
+        if (!hip_ok(hipGetLastError())) return HEINSEN_ERR_HIP;
+        const hs::LaunchTag gtag{0, 0, true};
+        hipError_t e = bnd ? hs::bnd_launch(c, sc.records, gtag) : hs::bdn_launch(c, sc.records, gtag);
+        return hip_ok(e) ? HEINSEN_OK : HEINSEN_ERR_HIP;
+    }
     std::lock_guard<std::mutex> lock(g_mutex);
     Scratch *s = nullptr;
-    hs::LaunchTag tag{0, 0};
+    hs::LaunchTag tag{0, 0, false};
     st = prepare_launch(c.stream, need, s, tag);
     if (st != HEINSEN_OK) return st;
     hipError_t e = bnd ? hs::bnd_launch(c, s->records, tag) : hs::bdn_launch(c, s->records, tag);
@@ -175,6 +220,7 @@ int heinsen_release_scratch(void)
         }
         (void)hipDeviceSynchronize();
         if (kv.second.records) (void)hipFree(kv.second.records);
+        for (unsigned long long *old : kv.second.retired) (void)hipFree(old);
     }
     g_scratch.clear();
     if (have_prev) (void)hipSetDevice(prev);

@@ -487,6 +487,7 @@ struct TileParams {
     uint32_t ntiles;       // rows * tpr
     uint32_t epoch;
     uint32_t ticket_base;
+    int from_header; // replayed from a graph: epoch and tickets come from the scratch header
     rec_t *ticket;
     rec_t *recs;           // per row: level-1 and level-2 summaries (2 records each), states (2 records each)
     uint32_t off2, off4, row_stride; // record offsets of level 2 and of the states inside a row's block
@@ -555,15 +556,19 @@ __global__ __launch_bounds__(kTileWaves * 64) void heinsen_scan_tiles(TileParams
     uint32_t tile = blockIdx.x;
     if (MULTI) {
         // tickets: a tile only ever waits for tiles with smaller tickets, which are already running
-        if (threadIdx.x == 0)
-            s_tile = __hip_atomic_fetch_add(reinterpret_cast<uint32_t *>(p.ticket), 1u, __ATOMIC_RELAXED,
-                                            __HIP_MEMORY_SCOPE_AGENT) - p.ticket_base;
+        if (threadIdx.x == 0) {
+            uint32_t *counter = reinterpret_cast<uint32_t *>(p.ticket + (p.from_header ? kHeaderGraphTicket : 0));
+            s_tile = __hip_atomic_fetch_add(counter, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) -
+                     (p.from_header ? 0u : p.ticket_base);
+        }
         __syncthreads();
         tile = __builtin_amdgcn_readfirstlane(s_tile);
         // a ticket outside the launch means the counter and the host's record of it have come apart
         // (an earlier launch on this stream died): touch nothing rather than index out of bounds
         if (tile >= p.ntiles) return;
     }
+    uint32_t epoch = p.epoch;
+    if (MULTI && p.from_header) epoch = header_word(p.ticket, kHeaderGraphEpoch);
     HS_STAMP(0);
     const int64_t row = tile / p.tpr;
     const uint32_t c = tile % p.tpr;
@@ -590,7 +595,7 @@ __global__ __launch_bounds__(kTileWaves * 64) void heinsen_scan_tiles(TileParams
         if (!got) {
             ra = rec_get(fp);
             rm = rec_get(fp + 1);
-            got = rec_ok(ra, p.epoch) && rec_ok(rm, p.epoch);
+            got = rec_ok(ra, epoch) && rec_ok(rm, epoch);
         }
         return __builtin_amdgcn_ballot_w64(got);
     };
@@ -655,7 +660,7 @@ __global__ __launch_bounds__(kTileWaves * 64) void heinsen_scan_tiles(TileParams
         }
         HS_STAMP(2);
         if (MULTI) {
-            if (more && r < 31u && lane == 0) seg_put<DOM>(rrow + 2 * (size_t)c, rrow + 2 * (size_t)c + 1, total, p.epoch);
+            if (more && r < 31u && lane == 0) seg_put<DOM>(rrow + 2 * (size_t)c, rrow + 2 * (size_t)c + 1, total, epoch);
             // The last tile of a group owes the later groups the summary of its group; it needs level 1
             // only and is published as soon as that is in, whatever else is still on its way.
             const bool lead = more && r == 31u;
@@ -671,7 +676,7 @@ __global__ __launch_bounds__(kTileWaves * 64) void heinsen_scan_tiles(TileParams
                     if (!pub2) {
                         a2 = seg_combine<DOM>(f1, total); // this group of 32 tiles
                         if (g < 31u && lane == 0)
-                            seg_put<DOM>(rrow + p.off2 + 2 * (size_t)(c >> 5), rrow + p.off2 + 2 * (size_t)(c >> 5) + 1, a2, p.epoch);
+                            seg_put<DOM>(rrow + p.off2 + 2 * (size_t)(c >> 5), rrow + p.off2 + 2 * (size_t)(c >> 5) + 1, a2, epoch);
                         pub2 = true;
                     }
                 }
@@ -694,8 +699,8 @@ __global__ __launch_bounds__(kTileWaves * 64) void heinsen_scan_tiles(TileParams
                 const State64 nx = seg_apply64<DOM>(st2, a2); // start of the next super-block
                 const unsigned long long bits = (unsigned long long)__double_as_longlong(nx.lx);
                 if (lane == 0) {
-                    rec_put(rrow + p.off4 + 2 * (size_t)(sb + 1), (uint32_t)(bits >> 32), p.epoch, SIGNED ? (nx.s >> 31) : 0u);
-                    rec_put(rrow + p.off4 + 2 * (size_t)(sb + 1) + 1, (uint32_t)bits, p.epoch, 0u);
+                    rec_put(rrow + p.off4 + 2 * (size_t)(sb + 1), (uint32_t)(bits >> 32), epoch, SIGNED ? (nx.s >> 31) : 0u);
+                    rec_put(rrow + p.off4 + 2 * (size_t)(sb + 1) + 1, (uint32_t)bits, epoch, 0u);
                 }
             }
             st = seg_apply64<DOM>(st2, f1);
@@ -845,6 +850,7 @@ hipError_t launch_mode(const ScanCall &c, const BdnPlan &pl, rec_t *records, Lau
     p.ntiles = pl.ntiles;
     p.epoch = tag.epoch;
     p.ticket_base = tag.ticket_base;
+    p.from_header = tag.from_header ? 1 : 0;
     p.ticket = records;
     p.recs = records ? records + kRecordBase : nullptr;
     p.off2 = pl.off2;

@@ -35,7 +35,8 @@ struct BndParams {
     uint32_t ntiles;  // ncols * nchunks
     uint32_t epoch;
     uint32_t ticket_base;
-    rec_t *ticket;    // word 0 of the record buffer
+    int from_header;  // replayed from a graph: epoch and tickets come from the scratch header
+    rec_t *ticket;    // word 0 of the record buffer (the scratch header)
     rec_t *agg;       // [ntiles][2][CH]  tile summaries: plane 0 = {A | signs}, plane 1 = {M}
     rec_t *state;     // [ngroups][ncols][CH] state at the start of a group: {log2|x| | sign}
 #ifdef HS_TRACE
@@ -137,12 +138,16 @@ __global__ __launch_bounds__(NW * 64, MINW) void heinsen_scan_bnd(BndParams p)
         const uint32_t q = p.ntiles >> 3, rem = p.ntiles & 7u;
         tile = die * q + (die < rem ? die : rem) + j;
     } else {
-        if (threadIdx.x == 0)
-            s_tile = __hip_atomic_fetch_add(reinterpret_cast<uint32_t *>(p.ticket), 1u, __ATOMIC_RELAXED,
-                                            __HIP_MEMORY_SCOPE_AGENT) - p.ticket_base;
+        if (threadIdx.x == 0) {
+            uint32_t *counter = reinterpret_cast<uint32_t *>(p.ticket + (p.from_header ? kHeaderGraphTicket : 0));
+            s_tile = __hip_atomic_fetch_add(counter, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) -
+                     (p.from_header ? 0u : p.ticket_base);
+        }
         __syncthreads();
         tile = __builtin_amdgcn_readfirstlane(s_tile);
     }
+    uint32_t epoch = p.epoch;
+    if (p.from_header) epoch = header_word(p.ticket, kHeaderGraphEpoch);
     // A ticket outside the launch can only mean that the counter and the host's record of it have come
     // apart (an earlier launch on this stream died): touch nothing rather than index out of bounds.
     if (tile >= p.ntiles) return;
@@ -206,13 +211,13 @@ __global__ __launch_bounds__(NW * 64, MINW) void heinsen_scan_bnd(BndParams p)
         bool ok = true;
         if (g > 0) {
 #pragma unroll
-            for (int v = 0; v < VEC; ++v) ok = ok && rec_ok(rS[v], p.epoch);
+            for (int v = 0; v < VEC; ++v) ok = ok && rec_ok(rS[v], epoch);
         }
 #pragma unroll
         for (int j = 0; j < G - 1; ++j) {
             if (j < r) {
 #pragma unroll
-                for (int v = 0; v < VEC; ++v) ok = ok && rec_ok(rA[j][v], p.epoch) && rec_ok(rM[j][v], p.epoch);
+                for (int v = 0; v < VEC; ++v) ok = ok && rec_ok(rA[j][v], epoch) && rec_ok(rM[j][v], epoch);
             }
         }
         return __builtin_amdgcn_ballot_w64(!ok) == 0ull;
@@ -314,7 +319,7 @@ __global__ __launch_bounds__(NW * 64, MINW) void heinsen_scan_bnd(BndParams p)
         if (more && r < G - 1) {
             rec_t *tp = p.agg + (size_t)tile * (2 * CH) + loff;
 #pragma unroll
-            for (int v = 0; v < VEC; ++v) seg_put<DOM>(tp + v, tp + CH + v, pre[v], p.epoch);
+            for (int v = 0; v < VEC; ++v) seg_put<DOM>(tp + v, tp + CH + v, pre[v], epoch);
         }
 #ifdef HS_TRACE
         if (threadIdx.x == 0) p.trace[(size_t)tile * 8 + 3] = t_begin; // slot 3: workgroup start, before the ticket
@@ -358,7 +363,7 @@ __global__ __launch_bounds__(NW * 64, MINW) void heinsen_scan_bnd(BndParams p)
 #pragma unroll
             for (int v = 0; v < VEC; ++v) {
                 State nx = seg_apply<DOM>(st[v], pre[v]);
-                rec_put(sp + v, f2u(nx.lx), p.epoch, SIGNED ? (nx.s >> 31) : 0u);
+                rec_put(sp + v, f2u(nx.lx), epoch, SIGNED ? (nx.s >> 31) : 0u);
             }
         }
     }
@@ -520,6 +525,7 @@ hipError_t launch_mode(const ScanCall &c, const BndPlan &pl, rec_t *records, Lau
     p.ntiles = pl.ntiles;
     p.epoch = tag.epoch;
     p.ticket_base = tag.ticket_base;
+    p.from_header = tag.from_header ? 1 : 0;
     p.ticket = records; // null when the launch needs no carries
     p.agg = records ? records + kRecordBase + pl.off_agg : nullptr;
     p.state = records ? records + kRecordBase + pl.off_state : nullptr;

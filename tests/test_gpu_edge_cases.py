@@ -336,7 +336,9 @@ def test_two_streams_use_separate_scratch(gpu):
         assert np.array_equal(out.cpu().numpy().view(np.uint32), single.view(np.uint32))
 
 
-def test_call_under_graph_capture_is_refused(gpu):
+def test_capture_without_existing_scratch_is_refused(gpu):
+    """A call that needs carries cannot allocate its scratch while its stream is capturing: on a stream
+    that has never run such a call it is refused, and nothing is recorded."""
     torch, hb = gpu
     cfg = workloads.CONFIGS[5].scaled(B=1, D=128, n=1024)
     from parity import to_device
@@ -351,6 +353,60 @@ def test_call_under_graph_capture_is_refused(gpu):
         finally:
             g.capture_end()
     assert st == hb.HEINSEN_ERR_UNSUPPORTED
+
+
+@pytest.mark.parametrize("layout,shape", [("BND", (2, 1500, 256)), ("BDN", (1, 2, 16384 * 5 + 24)), ("BND", (40, 700, 8))])
+def test_calls_with_carries_can_be_captured_once_the_stream_has_scratch(gpu, layout, shape):
+    """After one ordinary call on the stream (a warm-up, which made the scratch) the same call may be
+    captured: replays take their launch epoch and tickets from the scratch header.  Three replays on fresh
+    inputs, with ordinary calls of this and of a larger shape (which replaces the stream's scratch) and
+    synchronisations in between, each checked against the oracle and bit for bit against the ordinary call."""
+    torch, hb = gpu
+    rng = np.random.default_rng(31)
+    if layout == "BND":
+        B, n, D = shape
+        big = (B, 2 * n, D)
+    else:
+        B, D, n = shape
+        big = (B, D, 2 * n)
+
+    def draw(shp):
+        return (rng.uniform(-1.05, 1.05, shp).astype(np.float32), rng.normal(0, 1, shp).astype(np.float32),
+                rng.normal(0, 1, B * D).astype(np.float32))
+
+    side = torch.cuda.Stream()
+    a_h, b_h, x_h = draw(shape)
+    a_t, b_t, x_t = (torch.from_numpy(v).cuda() for v in (a_h, b_h, x_h))
+    out_g = torch.zeros(shape, dtype=torch.float32, device="cuda")
+    out_e = torch.zeros(shape, dtype=torch.float32, device="cuda")
+    ab_big = [torch.from_numpy(v).cuda() for v in draw(big)]
+    out_big = torch.zeros(big, dtype=torch.float32, device="cuda")
+    torch.cuda.synchronize()
+    with torch.cuda.stream(side):
+        hb.heinsen_scan(a_t, b_t, x_t, out_e, B, D, n, hb.LAYOUTS[layout], 0, side)  # warm-up: allocates the scratch
+    side.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g, stream=side):
+        hb.heinsen_scan(a_t, b_t, x_t, out_g, B, D, n, hb.LAYOUTS[layout], 0, torch.cuda.current_stream())
+    for rep in range(3):
+        a_h, b_h, x_h = draw(shape)
+        a_t.copy_(torch.from_numpy(a_h))
+        b_t.copy_(torch.from_numpy(b_h))
+        x_t.copy_(torch.from_numpy(x_h))
+        out_g.zero_()
+        torch.cuda.synchronize()
+        with torch.cuda.stream(side):
+            g.replay()
+        side.synchronize()
+        with torch.cuda.stream(side):
+            hb.heinsen_scan(a_t, b_t, x_t, out_e, B, D, n, hb.LAYOUTS[layout], 0, side)
+            if rep == 1:  # a larger ordinary call replaces the stream's scratch; the graph keeps the old one
+                nb = big[1] if layout == "BND" else big[2]
+                hb.heinsen_scan(ab_big[0], ab_big[1], ab_big[2], out_big, B, D, nb, hb.LAYOUTS[layout], 0, side)
+        side.synchronize()
+        got = out_g.cpu().numpy()
+        assert np.array_equal(got.view(np.uint32), out_e.cpu().numpy().view(np.uint32)), f"replay {rep} differs from the ordinary call"
+        _assert_signed(got.astype(np.float64), _ref(a_h, b_h, x_h, layout), layout)
 
 
 @pytest.mark.parametrize("layout,shape", [("BDN", (2, 8, 2048)), ("BDN", (70, 1, 16384)), ("BND", (2, 64, 128)), ("BDN", (64, 4, 64)), ("BND", (40, 33, 8))])
