@@ -22,15 +22,17 @@ struct ScanCall {
 };
 
 // Scratch is one buffer of 64-bit tagged records per (device, stream) (see heinsen_math.hpp).  Header
-// words: 0 = ticket counter of ordinary launches, 1 = ticket counter and 2 = epoch of launches replayed
-// from a HIP graph; carry records start at kRecordBase.  Every launch gets a fresh epoch, so the buffer
-// never needs clearing.  An ordinary launch gets its epoch (even) and `ticket_base`, the value word 0
-// has when the launch starts, from the host, which adds the tickets drawn after every launch.  A launch
-// recorded into a graph cannot: the same kernel arguments are replayed many times.  It reads its epoch
-// (odd) from word 2 and draws tickets from word 1, both set by a one-workgroup kernel recorded in front
-// of it (heinsen_api.hip), and leaves word 0 and the host's copy of it alone.
-constexpr size_t kRecordBase = 8;
-constexpr size_t kHeaderGraphTicket = 1, kHeaderGraphEpoch = 2;
+// words: 0 = ticket counter of ordinary launches, 1 = ticket counter and 16 = epoch of launches replayed
+// from a HIP graph; carry records start at kRecordBase.  (The epoch, which every workgroup reads, has a
+// 128-byte line of its own: on the line of a ticket counter its readers would queue with the atomics.)
+// Every launch gets a fresh epoch, so the buffer never needs clearing.  An ordinary launch gets its
+// epoch (even) and `ticket_base`, the value word 0 has when the launch starts, from the host, which
+// adds the tickets drawn after every launch.  A launch recorded into a graph cannot: the same kernel
+// arguments are replayed many times.  It reads its epoch (odd) from word 16 and draws tickets from
+// word 1, both set by a one-workgroup kernel recorded in front of it (heinsen_api.hip), and leaves
+// word 0 and the host's copy of it alone.
+constexpr size_t kRecordBase = 32;
+constexpr size_t kHeaderGraphTicket = 1, kHeaderGraphEpoch = 16;
 
 struct LaunchTag {
     uint32_t epoch;       // 2, 4, .. 2^30 - 2 (ignored when from_header)

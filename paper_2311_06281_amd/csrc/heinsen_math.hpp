@@ -359,13 +359,6 @@ __device__ __forceinline__ bool rec_ok(rec_t r, uint32_t epoch) { return ((uint3
 __device__ __forceinline__ uint32_t rec_payload(rec_t r) { return (uint32_t)r; }
 __device__ __forceinline__ uint32_t rec_bits(rec_t r) { return (uint32_t)(r >> 32) & 3u; }
 
-// Epoch of a launch replayed from a graph: word `index` of the scratch header, read once per wave.
-__device__ __forceinline__ uint32_t header_word(const rec_t *header, int index)
-{
-    const uint32_t v = __hip_atomic_load(reinterpret_cast<const uint32_t *>(header + index), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    return (uint32_t)__builtin_amdgcn_readfirstlane((int)v);
-}
-
 // A segment summary is two records: {A, tag | sA, sM} and {M, tag}.
 template <int DOM>
 __device__ __forceinline__ void seg_put(rec_t *pa, rec_t *pm, const Seg &g, uint32_t epoch)

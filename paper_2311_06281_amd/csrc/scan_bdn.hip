@@ -545,6 +545,7 @@ __global__ __launch_bounds__(kTileWaves * 64) void heinsen_scan_tiles(TileParams
     constexpr int kTile = NW * 64 * ITEMS; // elements per tile
     static_assert(!MULTI || ITEMS == kTileItems, "rows of several tiles use the full tile");
     __shared__ uint32_t s_tile;
+    __shared__ uint32_t s_epoch;
     __shared__ float lds_A[NW], lds_M[NW];
     __shared__ uint32_t lds_S[NW];
     __shared__ float lds_startL;
@@ -560,6 +561,8 @@ __global__ __launch_bounds__(kTileWaves * 64) void heinsen_scan_tiles(TileParams
             uint32_t *counter = reinterpret_cast<uint32_t *>(p.ticket + (p.from_header ? kHeaderGraphTicket : 0));
             s_tile = __hip_atomic_fetch_add(counter, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) -
                      (p.from_header ? 0u : p.ticket_base);
+            // a replayed launch finds its epoch in the header (written by the kernel recorded before this one)
+            s_epoch = p.from_header ? (uint32_t)p.ticket[kHeaderGraphEpoch] : p.epoch;
         }
         __syncthreads();
         tile = __builtin_amdgcn_readfirstlane(s_tile);
@@ -567,8 +570,7 @@ __global__ __launch_bounds__(kTileWaves * 64) void heinsen_scan_tiles(TileParams
         // (an earlier launch on this stream died): touch nothing rather than index out of bounds
         if (tile >= p.ntiles) return;
     }
-    uint32_t epoch = p.epoch;
-    if (MULTI && p.from_header) epoch = header_word(p.ticket, kHeaderGraphEpoch);
+    const uint32_t epoch = MULTI ? (uint32_t)__builtin_amdgcn_readfirstlane((int)s_epoch) : 0u;
     HS_STAMP(0);
     const int64_t row = tile / p.tpr;
     const uint32_t c = tile % p.tpr;

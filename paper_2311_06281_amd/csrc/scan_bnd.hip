@@ -112,6 +112,7 @@ __global__ __launch_bounds__(NW * 64, MINW) void heinsen_scan_bnd(BndParams p)
     constexpr int GP = G > 1 ? G - 1 : 1;
     static_assert(T <= 32, "one sign word per channel");
     __shared__ uint32_t s_tile;
+    __shared__ uint32_t s_epoch;
     __shared__ float lds_A[NW][CH];
     __shared__ float lds_M[NW][CH];
     __shared__ uint32_t lds_S[NW][CH];
@@ -142,12 +143,13 @@ __global__ __launch_bounds__(NW * 64, MINW) void heinsen_scan_bnd(BndParams p)
             uint32_t *counter = reinterpret_cast<uint32_t *>(p.ticket + (p.from_header ? kHeaderGraphTicket : 0));
             s_tile = __hip_atomic_fetch_add(counter, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) -
                      (p.from_header ? 0u : p.ticket_base);
+            // a replayed launch finds its epoch in the header (written by the kernel recorded before this one)
+            s_epoch = p.from_header ? (uint32_t)p.ticket[kHeaderGraphEpoch] : p.epoch;
         }
         __syncthreads();
         tile = __builtin_amdgcn_readfirstlane(s_tile);
     }
-    uint32_t epoch = p.epoch;
-    if (p.from_header) epoch = header_word(p.ticket, kHeaderGraphEpoch);
+    const uint32_t epoch = p.ticket != nullptr ? (uint32_t)__builtin_amdgcn_readfirstlane((int)s_epoch) : 0u;
     // A ticket outside the launch can only mean that the counter and the host's record of it have come
     // apart (an earlier launch on this stream died): touch nothing rather than index out of bounds.
     if (tile >= p.ntiles) return;
