@@ -472,6 +472,9 @@ __global__ __launch_bounds__(256, 4) void heinsen_scan_rows_packed(PackedParams 
 // summary is published as soon as the level-1 summaries it is made of are in, so no tile waits for
 // another tile's wait; only the super-block states form a chain, n / (1024 * tile) links long.
 
+// records per summary slot: the two records of a summary (or state) get a 128-byte line of their own, so
+// that the tiles polling for one summary do not queue with the accesses to its neighbours
+constexpr uint32_t kRecStride = 16;
 constexpr int kTileWaves = 8;   // waves per workgroup
 constexpr int kTileItems = 32;  // elements per lane (rows of one tile may use 8 or 16: a shorter serial chain)
 constexpr int kTile = kTileWaves * 64 * kTileItems;
@@ -588,9 +591,9 @@ __global__ __launch_bounds__(kTileWaves * 64) void heinsen_scan_tiles(TileParams
         // lanes 0-30: level 2 (earlier groups of the super-block), lane 31: the super-block state,
         // lanes 32-62: level 1 (earlier tiles of the group)
         const uint32_t sub = (uint32_t)lane & 31u;
-        if (lane < 31 && sub < g) { need = true; fp = rrow + p.off2 + 2 * (size_t)(((c >> 10) << 5) + sub); }
-        if (lane == 31 && sb > 0) { need = true; fp = rrow + p.off4 + 2 * (size_t)sb; }
-        if (lane >= 32 && lane < 63 && sub < r) { need = true; fp = rrow + 2 * (size_t)(((c >> 5) << 5) + sub); }
+        if (lane < 31 && sub < g) { need = true; fp = rrow + p.off2 + kRecStride * (size_t)(((c >> 10) << 5) + sub); }
+        if (lane == 31 && sb > 0) { need = true; fp = rrow + p.off4 + kRecStride * (size_t)sb; }
+        if (lane >= 32 && lane < 63 && sub < r) { need = true; fp = rrow + kRecStride * (size_t)(((c >> 5) << 5) + sub); }
     }
     bool got = !need; // this lane's records are in
     auto fetch_records = [&]() -> uint64_t {
@@ -662,7 +665,7 @@ __global__ __launch_bounds__(kTileWaves * 64) void heinsen_scan_tiles(TileParams
         }
         HS_STAMP(2);
         if (MULTI) {
-            if (more && r < 31u && lane == 0) seg_put<DOM>(rrow + 2 * (size_t)c, rrow + 2 * (size_t)c + 1, total, epoch);
+            if (more && r < 31u && lane == 0) seg_put<DOM>(rrow + kRecStride * (size_t)c, rrow + kRecStride * (size_t)c + 1, total, epoch);
             // The last tile of a group owes the later groups the summary of its group; it needs level 1
             // only and is published as soon as that is in, whatever else is still on its way.
             const bool lead = more && r == 31u;
@@ -678,7 +681,7 @@ __global__ __launch_bounds__(kTileWaves * 64) void heinsen_scan_tiles(TileParams
                     if (!pub2) {
                         a2 = seg_combine<DOM>(f1, total); // this group of 32 tiles
                         if (g < 31u && lane == 0)
-                            seg_put<DOM>(rrow + p.off2 + 2 * (size_t)(c >> 5), rrow + p.off2 + 2 * (size_t)(c >> 5) + 1, a2, epoch);
+                            seg_put<DOM>(rrow + p.off2 + kRecStride * (size_t)(c >> 5), rrow + p.off2 + kRecStride * (size_t)(c >> 5) + 1, a2, epoch);
                         pub2 = true;
                     }
                 }
@@ -701,8 +704,8 @@ __global__ __launch_bounds__(kTileWaves * 64) void heinsen_scan_tiles(TileParams
                 const State64 nx = seg_apply64<DOM>(st2, a2); // start of the next super-block
                 const unsigned long long bits = (unsigned long long)__double_as_longlong(nx.lx);
                 if (lane == 0) {
-                    rec_put(rrow + p.off4 + 2 * (size_t)(sb + 1), (uint32_t)(bits >> 32), epoch, SIGNED ? (nx.s >> 31) : 0u);
-                    rec_put(rrow + p.off4 + 2 * (size_t)(sb + 1) + 1, (uint32_t)bits, epoch, 0u);
+                    rec_put(rrow + p.off4 + kRecStride * (size_t)(sb + 1), (uint32_t)(bits >> 32), epoch, SIGNED ? (nx.s >> 31) : 0u);
+                    rec_put(rrow + p.off4 + kRecStride * (size_t)(sb + 1) + 1, (uint32_t)bits, epoch, 0u);
                 }
             }
             st = seg_apply64<DOM>(st2, f1);
@@ -787,9 +790,9 @@ BdnPlan make_plan(const ScanCall &c)
     pl.tile_items = c.n <= kTileWaves * 64 * 8 ? 8 : (c.n <= kTileWaves * 64 * 16 ? 16 : kTileItems);
     if (!pl.multi) return pl;
     const uint32_t n1 = pl.tpr, n2 = (pl.tpr + 31) / 32, n4 = (pl.tpr + 1023) / 1024 + 1;
-    pl.off2 = 2 * n1;
-    pl.off4 = pl.off2 + 2 * n2;
-    pl.row_stride = pl.off4 + 2 * n4;
+    pl.off2 = kRecStride * n1;
+    pl.off4 = pl.off2 + kRecStride * n2;
+    pl.row_stride = pl.off4 + kRecStride * n4;
     pl.records = (size_t)pl.rows * pl.row_stride;
     return pl;
 }
