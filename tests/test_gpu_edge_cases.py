@@ -101,6 +101,29 @@ def test_b_zero_is_running_product_and_a_one_is_running_sum(gpu, layout, shape):
     _assert_signed(got, ref, layout)
 
 
+@pytest.mark.parametrize("layout,shape", SHAPES)
+def test_wide_dynamic_range(gpu, layout, shape):
+    """Coefficients and inputs spread over many orders of magnitude with random signs (|a| log-normal with
+    sigma 3 around e^-1, |b| log-normal with sigma 5): every term is carried as a logarithm, so nothing
+    overflows or flushes on the way as long as the values themselves fit float32."""
+    rng = np.random.default_rng(13)
+    sgn = lambda shp: np.where(rng.random(shp) < 0.5, -1.0, 1.0)
+    a = (sgn(shape) * np.exp(rng.normal(-1.0, 3.0, shape))).astype(np.float32)
+    b = (sgn(shape) * np.exp(rng.normal(0.0, 5.0, shape))).astype(np.float32)
+    B = shape[0]
+    D = shape[2] if layout == "BND" else shape[1]
+    x0 = (sgn(B * D) * np.exp(rng.normal(0.0, 5.0, B * D))).astype(np.float32)
+    ref = _ref(a, b, x0, layout)
+    assert np.isfinite(ref).all() and np.abs(ref).max() < 1e30  # the data, not the kernel, keeps x inside float32
+    got = _scan(gpu, a, b, x0, layout)
+    assert np.isfinite(got).all()
+    # running scale over s = 0..t: x_0 is huge for some channels and the first steps decay from it
+    axis = 1 if layout == "BND" else 2
+    shp = (B, 1, D) if layout == "BND" else (B, D, 1)
+    scale = np.maximum(np.maximum.accumulate(np.abs(ref), axis=axis), np.abs(x0.astype(np.float64)).reshape(shp))
+    assert np.all(np.abs(got - ref) <= SIGNED_RTOL * scale), float(np.max(np.abs(got - ref) / scale))
+
+
 def test_all_zero_inputs_and_zero_x0(gpu):
     for layout, shape in SHAPES:
         B = shape[0]
