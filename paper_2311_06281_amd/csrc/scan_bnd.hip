@@ -482,6 +482,7 @@ BndPlan make_plan(const ScanCall &c)
     pl.CH = 64 * pl.vec;
     pl.cols_per_b = (int)ceil_div(c.D, pl.CH);
     pl.ncols = (int)(c.B * pl.cols_per_b);
+
     pl.dp_shift = 6;
     pl.bpack = 1;
     if (c.D <= 32 && c.B > 1 && pl.variant == 0) {
@@ -494,6 +495,10 @@ BndPlan make_plan(const ScanCall &c)
             pl.ncols = (int)ceil_div(c.B, pl.bpack);
         }
     }
+    // Few columns: the states handed from group to group (0.9 us per link) bound the launch, not the
+    // memory; groups of eight tiles halve the chain (1 x 2^19 x 256: 36 % -> 45 % of HBM peak; with many
+    // columns the longer fold costs 1-2 %).  Not where the extra records would spill registers.
+    if (pl.variant == 0 && pl.NW == 8 && pl.T == 32 && pl.ncols < 64 && pl.bpack == 1 && !(c.log_in && c.log_out)) pl.G = 8;
     pl.nchunks = (int)ceil_div(c.n, (int64_t)pl.NW * pl.T);
     pl.ngroups = (int)ceil_div(pl.nchunks, pl.G);
     pl.ntiles = (uint32_t)pl.ncols * (uint32_t)pl.nchunks;
@@ -561,6 +566,12 @@ hipError_t launch_mode(const ScanCall &c, const BndPlan &pl, rec_t *records, Lau
     } else {
 #define HS_BND(NW_, PACKB_) \
     hipLaunchKernelGGL((heinsen_scan_bnd<DOM, LOG_IN, LOG_OUT, InT, 1, 32, NW_, 4, 4, true, PACKB_>), grid, block, 0, c.stream, p)
+        if constexpr (!(LOG_IN && LOG_OUT)) {
+            if (pl.G == 8) {
+                hipLaunchKernelGGL((heinsen_scan_bnd<DOM, LOG_IN, LOG_OUT, InT, 1, 32, 8, 8, 4, true, false>), grid, block, 0, c.stream, p);
+                return hipGetLastError();
+            }
+        }
         if (pl.bpack > 1) {
             if (pl.NW == 1) HS_BND(1, true);
             else if (pl.NW == 2) HS_BND(2, true);
