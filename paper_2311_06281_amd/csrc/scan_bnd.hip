@@ -39,6 +39,8 @@ struct BndParams {
     rec_t *ticket;    // word 0 of the record buffer (the scratch header)
     rec_t *agg;       // [ntiles][2][CH]  tile summaries: plane 0 = {A | signs}, plane 1 = {M}
     rec_t *state;     // [ngroups][ncols][CH] state at the start of a group: {log2|x| | sign}
+                      // (SG > 0: [nsuper][ncols][CH], at the start of a super-group of SG groups)
+    rec_t *gagg;      // SG > 0: [ngroups][ncols][2][CH] group summaries, planes as in agg
 #ifdef HS_TRACE
     unsigned long long *trace; // [ntiles][8] wall-clock stamps of wave 0 (100 MHz), development only
 #endif
@@ -104,7 +106,11 @@ __device__ __forceinline__ void unpack_signs(uint32_t s, Seg &g)
 // across time steps (bounds register pressure).  PACKB: fewer than 64 channels -- the 64 lanes of a column
 // are the channels of several batch items side by side (same tiles, carries and arithmetic; only the
 // lane -> memory mapping differs, and a wave's accesses are then pieces of D elements, one per batch item).
-template <int DOM, bool LOG_IN, bool LOG_OUT, typename InT, int VEC, int T, int NW, int G, int MINW, bool SB, bool PACKB = false>
+// SG > 0: a second carry level for launches of few columns, where the chain of group states would bound
+// the launch: the last tile of a group also publishes the summary of its group, states are handed on only
+// from one super-group of SG groups to the next, and a tile folds the summaries of the earlier groups of
+// its super-group (a second round of record loads, into the registers of the first).
+template <int DOM, bool LOG_IN, bool LOG_OUT, typename InT, int VEC, int T, int NW, int G, int MINW, bool SB, bool PACKB = false, int SG = 0>
 __global__ __launch_bounds__(NW * 64, MINW) void heinsen_scan_bnd(BndParams p)
 {
     constexpr bool SIGNED = DOM == kSigned;
@@ -191,8 +197,11 @@ __global__ __launch_bounds__(NW * 64, MINW) void heinsen_scan_bnd(BndParams p)
     //      kernel is past its first round the earlier tiles of the group have usually published, and the
     //      records then arrive ahead of the tile's own loads at no cost in latency --------------------
     rec_t rA[GP][VEC], rM[GP][VEC], rS[VEC];
+    static_assert(SG == 0 || (SG <= G && G > 1), "the second round of records reuses the registers of the first");
+    const int q = SG > 0 ? g / (SG > 0 ? SG : 1) : 0;  // super-group, and the group's place in it
+    const int gi = SG > 0 ? g % (SG > 0 ? SG : 1) : 0;
     auto issue_records = [&]() {
-        if (g > 0) {
+        if (SG == 0 && g > 0) {
             const rec_t *sp = p.state + ((size_t)g * p.ncols + col) * CH + loff;
 #pragma unroll
             for (int v = 0; v < VEC; ++v) rS[v] = rec_get(sp + v);
@@ -211,7 +220,7 @@ __global__ __launch_bounds__(NW * 64, MINW) void heinsen_scan_bnd(BndParams p)
     };
     auto records_in = [&]() -> bool {
         bool ok = true;
-        if (g > 0) {
+        if (SG == 0 && g > 0) {
 #pragma unroll
             for (int v = 0; v < VEC; ++v) ok = ok && rec_ok(rS[v], epoch);
         }
@@ -334,6 +343,98 @@ __global__ __launch_bounds__(NW * 64, MINW) void heinsen_scan_bnd(BndParams p)
         }
         HS_STAMP(4);
         State st[VEC];
+        if constexpr (SG > 0) {
+            // the earlier tiles of the group as one summary; the last tile of a group owes the later groups
+            // of its super-group the summary of the whole group (no state needed for it)
+            Seg grp[VEC];
+#pragma unroll
+            for (int v = 0; v < VEC; ++v) grp[v] = seg_identity<DOM>();
+#pragma unroll
+            for (int j = 0; j < G - 1; ++j) {
+                if (j < r) {
+#pragma unroll
+                    for (int v = 0; v < VEC; ++v) grp[v] = seg_combine<DOM>(grp[v], seg_from<DOM>(rA[j][v], rM[j][v]));
+                }
+            }
+            if (more && r == G - 1 && gi < SG - 1) {
+                rec_t *gp = p.gagg + ((size_t)g * p.ncols + col) * (2 * CH) + loff;
+#pragma unroll
+                for (int v = 0; v < VEC; ++v) seg_put<DOM>(gp + v, gp + CH + v, seg_combine<DOM>(grp[v], pre[v]), epoch);
+            }
+            // second round: the state at the start of the super-group and the earlier groups of it
+            auto issue2 = [&]() {
+                if (q > 0) {
+                    const rec_t *sp = p.state + ((size_t)q * p.ncols + col) * CH + loff;
+#pragma unroll
+                    for (int v = 0; v < VEC; ++v) rS[v] = rec_get(sp + v);
+                }
+#pragma unroll
+                for (int j = 0; j < SG - 1; ++j) {
+                    if (j < gi) {
+                        const rec_t *gp = p.gagg + ((size_t)(q * SG + j) * p.ncols + col) * (2 * CH) + loff;
+#pragma unroll
+                        for (int v = 0; v < VEC; ++v) {
+                            rA[j][v] = rec_get(gp + v);
+                            rM[j][v] = rec_get(gp + CH + v);
+                        }
+                    }
+                }
+            };
+            auto in2 = [&]() -> bool {
+                bool ok = true;
+                if (q > 0) {
+#pragma unroll
+                    for (int v = 0; v < VEC; ++v) ok = ok && rec_ok(rS[v], epoch);
+                }
+#pragma unroll
+                for (int j = 0; j < SG - 1; ++j) {
+                    if (j < gi) {
+#pragma unroll
+                        for (int v = 0; v < VEC; ++v) ok = ok && rec_ok(rA[j][v], epoch) && rec_ok(rM[j][v], epoch);
+                    }
+                }
+                return __builtin_amdgcn_ballot_w64(!ok) == 0ull;
+            };
+            issue2();
+            while (!in2()) {
+                __builtin_amdgcn_s_sleep(2);
+                issue2();
+            }
+#pragma unroll
+            for (int v = 0; v < VEC; ++v) {
+                if (q == 0) {
+                    float x0v = LOG_IN ? 0.0f : 1.0f;
+                    if (chan_ok) x0v = p.x0[p.x0_stride ? (x0_at + v) : 0];
+                    encode<DOM, LOG_IN>(x0v, st[v].lx, st[v].s);
+                } else {
+                    st[v].lx = u2f(rec_payload(rS[v]));
+                    st[v].s = SIGNED ? (rec_bits(rS[v]) << 31) : 0u;
+                }
+            }
+#pragma unroll
+            for (int j = 0; j < SG - 1; ++j) {
+                if (j < gi) {
+#pragma unroll
+                    for (int v = 0; v < VEC; ++v) st[v] = seg_apply<DOM>(st[v], seg_from<DOM>(rA[j][v], rM[j][v]));
+                }
+            }
+#pragma unroll
+            for (int v = 0; v < VEC; ++v) {
+                st[v] = seg_apply<DOM>(st[v], grp[v]);
+                lds_startL[loff + v] = st[v].lx;
+                lds_startS[loff + v] = st[v].s;
+            }
+            HS_STAMP(5);
+            // last tile of a super-group: the state after this tile starts the next one
+            if (more && r == G - 1 && gi == SG - 1) {
+                rec_t *sp = p.state + ((size_t)(q + 1) * p.ncols + col) * CH + loff;
+#pragma unroll
+                for (int v = 0; v < VEC; ++v) {
+                    State nx = seg_apply<DOM>(st[v], pre[v]);
+                    rec_put(sp + v, f2u(nx.lx), epoch, SIGNED ? (nx.s >> 31) : 0u);
+                }
+            }
+        } else {
 #pragma unroll
         for (int v = 0; v < VEC; ++v) {
             if (g == 0) {
@@ -367,6 +468,7 @@ __global__ __launch_bounds__(NW * 64, MINW) void heinsen_scan_bnd(BndParams p)
                 State nx = seg_apply<DOM>(st[v], pre[v]);
                 rec_put(sp + v, f2u(nx.lx), epoch, SIGNED ? (nx.s >> 31) : 0u);
             }
+        }
         }
     }
     __syncthreads();
@@ -420,7 +522,8 @@ struct BndPlan {
     int dp_shift, bpack; // bpack > 1: narrow rows, the channels of bpack batch items share a 64-lane column
     int cols_per_b, ncols, nchunks, ngroups;
     uint32_t ntiles;
-    size_t off_agg, off_state, records; // in records, relative to kRecordBase
+    int SG;             // > 0: groups per super-group (second carry level)
+    size_t off_agg, off_gagg, off_state, records; // in records, relative to kRecordBase
 };
 
 #ifdef HS_TUNING
@@ -496,15 +599,30 @@ BndPlan make_plan(const ScanCall &c)
         }
     }
     // Few columns: the states handed from group to group (0.9 us per link) bound the launch, not the
-    // memory; groups of eight tiles halve the chain (1 x 2^19 x 256: 36 % -> 45 % of HBM peak; with many
-    // columns the longer fold costs 1-2 %).  Not where the extra records would spill registers.
-    if (pl.variant == 0 && pl.NW == 8 && pl.T == 32 && pl.ncols < 64 && pl.bpack == 1 && !(c.log_in && c.log_out)) pl.G = 8;
+    // memory.  Below 64 columns the groups are eight tiles long (half the links); up to 8 columns a second
+    // carry level hands states on only between super-groups (4 x 4 tiles: n / 4096 links, no spills; one
+    // or two columns: 8 x 8 tiles, n / 16384 links, at the price of some spilled registers).  With many
+    // columns the longer folds and the second round of record loads would cost a few percent.  Not for the
+    // modes whose kernels are short of registers already.
+    pl.SG = 0;
+    if (pl.variant == 0 && pl.NW == 8 && pl.T == 32 && pl.bpack == 1 && !(c.log_in && c.log_out)) {
+        if (pl.ncols <= 2) {
+            pl.G = 8;
+            pl.SG = 8;
+        } else if (pl.ncols <= 8) {
+            pl.G = 4;
+            pl.SG = 4;
+        } else if (pl.ncols < 64) {
+            pl.G = 8;
+        }
+    }
     pl.nchunks = (int)ceil_div(c.n, (int64_t)pl.NW * pl.T);
     pl.ngroups = (int)ceil_div(pl.nchunks, pl.G);
     pl.ntiles = (uint32_t)pl.ncols * (uint32_t)pl.nchunks;
     pl.off_agg = 0;
-    pl.off_state = (size_t)pl.ntiles * 2 * pl.CH;
-    pl.records = pl.off_state + (size_t)pl.ngroups * pl.ncols * pl.CH;
+    pl.off_gagg = (size_t)pl.ntiles * 2 * pl.CH;
+    pl.off_state = pl.off_gagg + (pl.SG ? (size_t)pl.ngroups * pl.ncols * 2 * pl.CH : 0);
+    pl.records = pl.off_state + (size_t)(pl.SG ? ceil_div(pl.ngroups, pl.SG) + 1 : pl.ngroups) * pl.ncols * pl.CH;
     pl.ticketless = pl.nchunks == 1 && c.n <= 64; // short single-tile columns: no records, no tickets
     if (pl.ticketless) pl.records = 0;
     return pl;
@@ -536,6 +654,7 @@ hipError_t launch_mode(const ScanCall &c, const BndPlan &pl, rec_t *records, Lau
     p.ticket = records; // null when the launch needs no carries
     p.agg = records ? records + kRecordBase + pl.off_agg : nullptr;
     p.state = records ? records + kRecordBase + pl.off_state : nullptr;
+    p.gagg = records ? records + kRecordBase + pl.off_gagg : nullptr;
 #ifdef HS_TRACE
     if (!g_trace) (void)hipMalloc(&g_trace, (size_t)(1u << 20) * 8 * sizeof(unsigned long long));
     p.trace = g_trace;
@@ -567,8 +686,13 @@ hipError_t launch_mode(const ScanCall &c, const BndPlan &pl, rec_t *records, Lau
 #define HS_BND(NW_, PACKB_) \
     hipLaunchKernelGGL((heinsen_scan_bnd<DOM, LOG_IN, LOG_OUT, InT, 1, 32, NW_, 4, 4, true, PACKB_>), grid, block, 0, c.stream, p)
         if constexpr (!(LOG_IN && LOG_OUT)) {
-            if (pl.G == 8) {
-                hipLaunchKernelGGL((heinsen_scan_bnd<DOM, LOG_IN, LOG_OUT, InT, 1, 32, 8, 8, 4, true, false>), grid, block, 0, c.stream, p);
+            if (pl.G == 8 || pl.SG > 0) {
+                if (pl.SG == 8)
+                    hipLaunchKernelGGL((heinsen_scan_bnd<DOM, LOG_IN, LOG_OUT, InT, 1, 32, 8, 8, 4, true, false, 8>), grid, block, 0, c.stream, p);
+                else if (pl.SG == 4)
+                    hipLaunchKernelGGL((heinsen_scan_bnd<DOM, LOG_IN, LOG_OUT, InT, 1, 32, 8, 4, 4, true, false, 4>), grid, block, 0, c.stream, p);
+                else
+                    hipLaunchKernelGGL((heinsen_scan_bnd<DOM, LOG_IN, LOG_OUT, InT, 1, 32, 8, 8, 4, true, false>), grid, block, 0, c.stream, p);
                 return hipGetLastError();
             }
         }

@@ -56,7 +56,9 @@ SHAPES = {
     "BDN": [(2, 3, 1), (1, 5, 17), (4, 8, 64), (3, 5, 256), (2, 70, 8), (1, 9, 100), (2, 3, 520), (1, 2, 2048), (1, 3, 2056), (1, 2, 6000), (1, 1, 12004), (1, 1, 16384 * 3 + 8),
             (3, 2, 16384 + 1)],
     "BND": [(2, 1, 5), (1, 17, 3), (2, 300, 64), (1, 257, 66), (1, 513, 130), (1, 40, 1000), (2, 1025, 7), (70, 40, 4), (9, 600, 32),
-            (5, 520, 2), (3, 1100, 33), (2, 100, 70), (4, 120, 8), (1, 256 * 19 + 5, 66)],
+            (5, 520, 2), (3, 1100, 33), (2, 100, 70), (4, 120, 8), (1, 256 * 19 + 5, 66),
+            # few columns: groups of eight tiles (20 columns), second carry level (3 columns: 4 x 4 tiles, 2 columns: 8 x 8)
+            (20, 256 * 19 + 5, 64), (3, 4096 * 2 + 700, 64), (1, 16384 * 2 + 300, 70)],
 }
 
 
