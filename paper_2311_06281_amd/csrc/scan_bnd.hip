@@ -605,7 +605,7 @@ BndPlan make_plan(const ScanCall &c)
     // columns the longer folds and the second round of record loads would cost a few percent.  Not for the
     // modes whose kernels are short of registers already.
     pl.SG = 0;
-    if (pl.variant == 0 && pl.NW == 8 && pl.T == 32 && pl.bpack == 1 && !(c.log_in && c.log_out)) {
+    if (pl.variant == 0 && pl.NW == 8 && pl.T == 32 && !(c.log_in && c.log_out)) {
         if (pl.ncols <= 2) {
             pl.G = 8;
             pl.SG = 8;
@@ -687,12 +687,18 @@ hipError_t launch_mode(const ScanCall &c, const BndPlan &pl, rec_t *records, Lau
     hipLaunchKernelGGL((heinsen_scan_bnd<DOM, LOG_IN, LOG_OUT, InT, 1, 32, NW_, 4, 4, true, PACKB_>), grid, block, 0, c.stream, p)
         if constexpr (!(LOG_IN && LOG_OUT)) {
             if (pl.G == 8 || pl.SG > 0) {
-                if (pl.SG == 8)
-                    hipLaunchKernelGGL((heinsen_scan_bnd<DOM, LOG_IN, LOG_OUT, InT, 1, 32, 8, 8, 4, true, false, 8>), grid, block, 0, c.stream, p);
-                else if (pl.SG == 4)
-                    hipLaunchKernelGGL((heinsen_scan_bnd<DOM, LOG_IN, LOG_OUT, InT, 1, 32, 8, 4, 4, true, false, 4>), grid, block, 0, c.stream, p);
-                else
-                    hipLaunchKernelGGL((heinsen_scan_bnd<DOM, LOG_IN, LOG_OUT, InT, 1, 32, 8, 8, 4, true, false>), grid, block, 0, c.stream, p);
+#define HS_BND_CARRY(G_, SG_, PACKB_) \
+    hipLaunchKernelGGL((heinsen_scan_bnd<DOM, LOG_IN, LOG_OUT, InT, 1, 32, 8, G_, 4, true, PACKB_, SG_>), grid, block, 0, c.stream, p)
+                if (pl.bpack > 1) {
+                    if (pl.SG == 8) HS_BND_CARRY(8, 8, true);
+                    else if (pl.SG == 4) HS_BND_CARRY(4, 4, true);
+                    else HS_BND_CARRY(8, 0, true);
+                } else {
+                    if (pl.SG == 8) HS_BND_CARRY(8, 8, false);
+                    else if (pl.SG == 4) HS_BND_CARRY(4, 4, false);
+                    else HS_BND_CARRY(8, 0, false);
+                }
+#undef HS_BND_CARRY
                 return hipGetLastError();
             }
         }

@@ -58,7 +58,9 @@ SHAPES = {
     "BND": [(2, 1, 5), (1, 17, 3), (2, 300, 64), (1, 257, 66), (1, 513, 130), (1, 40, 1000), (2, 1025, 7), (70, 40, 4), (9, 600, 32),
             (5, 520, 2), (3, 1100, 33), (2, 100, 70), (4, 120, 8), (1, 256 * 19 + 5, 66),
             # few columns: groups of eight tiles (20 columns), second carry level (3 columns: 4 x 4 tiles, 2 columns: 8 x 8)
-            (20, 256 * 19 + 5, 64), (3, 4096 * 2 + 700, 64), (1, 16384 * 2 + 300, 70)],
+            (20, 256 * 19 + 5, 64), (3, 4096 * 2 + 700, 64), (1, 16384 * 2 + 300, 70),
+            # the same with narrow channels (several batch items per column)
+            (20, 4096 * 2 + 700, 8), (5, 16384 * 2 + 300, 2), (300, 256 * 9 + 1, 4)],
 }
 
 
