@@ -9,6 +9,10 @@
 // bit-reproducible) onto the state at the start of the group, and the last tile of a group publishes
 // the state at the start of the next.  Every element is read once and written once.
 //
+// Variations chosen on the host (make_plan): fewer waves per tile for short sequences, no tickets at
+// all when a column is one short tile; with few columns, longer groups and a second carry level (SG);
+// with fewer than 33 channels, several batch items side by side in the lanes of a column (PACKB).
+//
 // What is computed is Sec. 4's expression applied by parts (Sec. 1, footnote on associativity); the
 // arithmetic is in heinsen_math.hpp.
 #include "heinsen_internal.hpp"
