@@ -134,3 +134,24 @@ def test_full_size_other_outputs(gpu, idx, mode):
         assert rel.max() < 0.2
         return
     assert nbad == 0, f"{nbad} of {ref.size} outside the tolerance (worst {worst:.3g})"
+
+
+@pytest.mark.parametrize("D,n", [(256, 1 << 19), (64, 1 << 20), (1024, 1 << 16)])
+def test_long_sequences_of_few_columns(gpu, D, n):
+    """[B,n,D] with 4, 1 and 16 columns of 64 channels and thousands of tiles along time: the launches whose
+    carry structure has longer groups and (for 4 and 1 columns) a second level, at a length where every
+    level is many records deep.  Configuration 2's distribution, generated and checked in full."""
+    torch, hb = gpu
+    import bench
+
+    cfg = workloads.CONFIGS[2].scaled(B=1, D=D, n=n)
+    print(f"[full] cfg2 distribution {cfg.shape()}", flush=True)
+    a, b, x0, out = bench.device_inputs(cfg, torch, distinct=1)
+    hb.heinsen_scan(a, b, x0, out, cfg.B, cfg.D, cfg.n, hb.LAYOUTS[cfg.layout], hb.flags_from_names(cfg.flags),
+                    torch.cuda.current_stream())
+    torch.cuda.synchronize()
+    got = out.cpu().numpy()
+    ref = reference(cfg, workloads.generate(cfg), threads=16)
+    nbad, worst = violations(cfg, got, ref)
+    print(f"[full] worst error/bound {worst:.3g}", flush=True)
+    assert nbad == 0, f"{nbad} of {ref.size} outside the tolerance (worst {worst:.3g})"
