@@ -66,7 +66,9 @@ typedef enum {
                                     without OUT_COMPLEX, OUT_COMPLEX with LOG_INPUTS, a call that needs
                                     scratch recorded into a graph on a stream that has none yet         */
     HEINSEN_ERR_ALLOC = 3,       /* scratch memory could not be allocated; nothing was launched          */
-    HEINSEN_ERR_HIP = 4          /* a HIP runtime call failed; see heinsen_last_hip_error()              */
+    HEINSEN_ERR_HIP = 4,         /* a HIP runtime call failed; see heinsen_last_hip_error()              */
+    HEINSEN_ERR_SCRATCH_LIMIT = 5 /* heinsen_scan_static only: the shape needs more scratch than its fixed
+                                    buffer holds; nothing was launched                                   */
 } heinsen_status_t;
 
 /*
@@ -116,6 +118,29 @@ typedef enum {
  */
 int heinsen_scan(const void *a_or_log_a, const void *b_or_log_b, const void *x0, void *out,
                  int64_t B, int64_t D, int64_t n, int layout, uint32_t flags, void *stream);
+
+/*
+ * heinsen_scan_static -- heinsen_scan for callers that cannot allocate device memory: code under HIP
+ * graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments, same kernels, same
+ * results bit for bit.  It never calls hipMalloc, hipFree or any allocating routine: the inter-tile
+ * carries live in a fixed 40 MiB device array that is part of the library (each GPU the library runs on
+ * holds its own copy until the process ends).
+ *
+ *   limit   : shapes whose carries do not fit are refused with HEINSEN_ERR_SCRATCH_LIMIT and nothing is
+ *             launched.  In records of 8 bytes, 32 + the following must stay within 5 * 2^20:
+ *               [B, n, D], n > 64 : about 128 * ceil(D/64) * B * ceil(n/256) * 1.125
+ *               [B, D, n], n > 16384 : about 16 * B * D * ceil(n/16384) * 1.04
+ *             (all five benchmark shapes fit; [16, 16384, 2048] float32 takes 36 MiB.)  Shapes that need
+ *             no carries have no limit.
+ *   sharing : every call on a GPU uses that GPU's one array, whatever the stream.  Calls that may run at
+ *             the same time on one GPU race on it and give wrong results: keep them on one stream or
+ *             order them with events.  heinsen_scan's own scratch is separate and never conflicts.
+ *   capture : may be recorded into a HIP graph; the first call on a device looks up the array's address
+ *             (hipGetSymbolAddress) and should be made outside a capture.
+ * Returns a heinsen_status_t.
+ */
+int heinsen_scan_static(const void *a_or_log_a, const void *b_or_log_b, const void *x0, void *out,
+                        int64_t B, int64_t D, int64_t n, int layout, uint32_t flags, void *stream);
 
 /* Static, NUL-terminated description of a heinsen_status_t value (never NULL). */
 const char *heinsen_status_string(int status);

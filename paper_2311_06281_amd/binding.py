@@ -32,8 +32,9 @@ HEINSEN_ERR_INVALID_ARG = 1
 HEINSEN_ERR_UNSUPPORTED = 2
 HEINSEN_ERR_ALLOC = 3
 HEINSEN_ERR_HIP = 4
+HEINSEN_ERR_SCRATCH_LIMIT = 5
 
-EXPORTS = ("heinsen_scan", "heinsen_status_string", "heinsen_last_hip_error", "heinsen_version",
+EXPORTS = ("heinsen_scan", "heinsen_scan_static", "heinsen_status_string", "heinsen_last_hip_error", "heinsen_version",
            "heinsen_release_scratch", "heinsen_kernel_name", "heinsen_sequential")
 
 _lib = None
@@ -55,6 +56,8 @@ def load() -> ctypes.CDLL:
         vp, i64, ci, u32 = ctypes.c_void_p, ctypes.c_int64, ctypes.c_int, ctypes.c_uint32
         lib.heinsen_scan.argtypes = [vp, vp, vp, vp, i64, i64, i64, ci, u32, vp]
         lib.heinsen_scan.restype = ci
+        lib.heinsen_scan_static.argtypes = [vp, vp, vp, vp, i64, i64, i64, ci, u32, vp]
+        lib.heinsen_scan_static.restype = ci
         lib.heinsen_status_string.argtypes = [ci]
         lib.heinsen_status_string.restype = ctypes.c_char_p
         lib.heinsen_last_hip_error.argtypes = []
@@ -133,6 +136,22 @@ def heinsen_scan(a, b, x0, out, B: int, D: int, n: int, layout: int, flags: int,
     if st != HEINSEN_OK:
         msg = heinsen_status_string(st)
         if st in (HEINSEN_ERR_HIP, HEINSEN_ERR_ALLOC):
+            msg += f", hipError_t {heinsen_last_hip_error()}"
+        raise HeinsenError(st, msg)
+
+
+def heinsen_scan_static_status(a, b, x0, out, B: int, D: int, n: int, layout: int, flags: int, stream=None) -> int:
+    """Raw call of the allocation-free variant: returns the heinsen_status_t instead of raising."""
+    return int(load().heinsen_scan_static(_addr(a), _addr(b), _addr(x0), _addr(out), int(B), int(D), int(n),
+                                          int(layout), int(flags), _stream_handle(stream)))
+
+
+def heinsen_scan_static(a, b, x0, out, B: int, D: int, n: int, layout: int, flags: int, stream=None) -> None:
+    """heinsen_scan without any device allocation (fixed scratch inside the library); see include/heinsen.h."""
+    st = heinsen_scan_static_status(a, b, x0, out, B, D, n, layout, flags, stream)
+    if st != HEINSEN_OK:
+        msg = heinsen_status_string(st)
+        if st == HEINSEN_ERR_HIP:
             msg += f", hipError_t {heinsen_last_hip_error()}"
         raise HeinsenError(st, msg)
 

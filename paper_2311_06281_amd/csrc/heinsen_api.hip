@@ -52,6 +52,14 @@ __global__ void heinsen_graph_prologue(unsigned long long *records, size_t capac
 std::mutex g_mutex;
 std::map<std::pair<int, hipStream_t>, Scratch> g_scratch;
 
+// Scratch of heinsen_scan_static: one fixed array per GPU, part of the loaded code, never allocated or
+// freed.  In host code the array's name is not a device address; the address on each device is looked
+// up once (hipGetSymbolAddress with that device current) and kept here.
+constexpr size_t kStaticRecords = ((size_t)40 << 20) / sizeof(unsigned long long); // 40 MiB
+static __device__ __align__(256) unsigned long long scratch[kStaticRecords];
+constexpr int kMaxDevices = 64;
+unsigned long long *g_static_scratch[kMaxDevices] = {};
+
 bool hip_ok(hipError_t e)
 {
     if (e != hipSuccess) {
@@ -134,16 +142,11 @@ int prepare_launch(hipStream_t stream, const hs::ScratchNeed &need, Scratch *&ou
     return HEINSEN_OK;
 }
 
-} // namespace
-
-extern "C" {
-
-int heinsen_scan(const void *a, const void *b, const void *x0, void *out, int64_t B, int64_t D, int64_t n,
-                 int layout, uint32_t flags, void *stream)
+// Checks the arguments of a scan call and fills `c`; `bnd` tells which layout path serves it.
+int make_call(const void *a, const void *b, const void *x0, void *out, int64_t B, int64_t D, int64_t n, int layout,
+              uint32_t flags, void *stream, hs::ScanCall &c, bool &bnd)
 {
     if (!a || !b || !x0 || !out) return HEINSEN_ERR_INVALID_ARG;
-    hs::ScanCall c = {};
-    bool bnd = false;
     int st = describe(B, D, n, layout, flags, c, bnd);
     if (st != HEINSEN_OK) return st;
     const uintptr_t in_align = c.bf16 ? 2 : 4;
@@ -155,6 +158,20 @@ int heinsen_scan(const void *a, const void *b, const void *x0, void *out, int64_
     c.x0 = static_cast<const float *>(x0);
     c.out = static_cast<float *>(out);
     c.stream = static_cast<hipStream_t>(stream);
+    return HEINSEN_OK;
+}
+
+} // namespace
+
+extern "C" {
+
+int heinsen_scan(const void *a, const void *b, const void *x0, void *out, int64_t B, int64_t D, int64_t n,
+                 int layout, uint32_t flags, void *stream)
+{
+    hs::ScanCall c = {};
+    bool bnd = false;
+    int st = make_call(a, b, x0, out, B, D, n, layout, flags, stream, c, bnd);
+    if (st != HEINSEN_OK) return st;
 
     const hs::ScratchNeed need = bnd ? hs::bnd_scratch(c) : hs::bdn_scratch(c);
     if (need.records == 0 && need.tickets == 0) {
@@ -191,6 +208,40 @@ int heinsen_scan(const void *a, const void *b, const void *x0, void *out, int64_
     return HEINSEN_OK;
 }
 
+int heinsen_scan_static(const void *a, const void *b, const void *x0, void *out, int64_t B, int64_t D, int64_t n,
+                        int layout, uint32_t flags, void *stream)
+{
+    hs::ScanCall c = {};
+    bool bnd = false;
+    int st = make_call(a, b, x0, out, B, D, n, layout, flags, stream, c, bnd);
+    if (st != HEINSEN_OK) return st;
+    const hs::ScratchNeed need = bnd ? hs::bnd_scratch(c) : hs::bdn_scratch(c);
+    if (need.records == 0 && need.tickets == 0) {
+        hipError_t e = bnd ? hs::bnd_launch(c, nullptr, hs::LaunchTag{0, 0, false}) : hs::bdn_launch(c, nullptr, hs::LaunchTag{0, 0, false});
+        return hip_ok(e) ? HEINSEN_OK : HEINSEN_ERR_HIP;
+    }
+    if (hs::kRecordBase + need.records > kStaticRecords) return HEINSEN_ERR_SCRATCH_LIMIT;
+    std::lock_guard<std::mutex> lock(g_mutex);
+    int dev = 0;
+    if (!hip_ok(hipGetDevice(&dev))) return HEINSEN_ERR_HIP;
+    if (dev < 0 || dev >= kMaxDevices) return HEINSEN_ERR_UNSUPPORTED;
+    if (g_static_scratch[dev] == nullptr) {
+        unsigned long long *ptr = nullptr;
+        if (!hip_ok(hipGetSymbolAddress(reinterpret_cast<void **>(&ptr), HIP_SYMBOL(scratch))) || ptr == nullptr)
+            return HEINSEN_ERR_HIP;
+        g_static_scratch[dev] = ptr;
+    }
+    unsigned long long *records = g_static_scratch[dev];
+    // The array keeps whatever the last call left in it.  Nothing has to be cleared: the one-workgroup
+    // kernel in front of the scan gives this call a launch counter no record in the array carries yet and
+    // a ticket counter at zero (and clears the records itself when the counter comes round).
+    hipLaunchKernelGGL(heinsen_graph_prologue, dim3(1), dim3(256), 0, c.stream, records, kStaticRecords);
+    if (!hip_ok(hipGetLastError())) return HEINSEN_ERR_HIP;
+    const hs::LaunchTag tag{0, 0, true};
+    hipError_t e = bnd ? hs::bnd_launch(c, records, tag) : hs::bdn_launch(c, records, tag);
+    return hip_ok(e) ? HEINSEN_OK : HEINSEN_ERR_HIP;
+}
+
 const char *heinsen_status_string(int status)
 {
     switch (status) {
@@ -199,6 +250,7 @@ const char *heinsen_status_string(int status)
     case HEINSEN_ERR_UNSUPPORTED: return "unsupported combination of arguments";
     case HEINSEN_ERR_ALLOC: return "scratch allocation failed";
     case HEINSEN_ERR_HIP: return "HIP runtime error";
+    case HEINSEN_ERR_SCRATCH_LIMIT: return "the call needs more scratch than the fixed buffer of heinsen_scan_static holds";
     default: return "unknown status";
     }
 }
