@@ -171,6 +171,59 @@ def fig1_sweep(torch, hb, runs=30):
     return points
 
 
+def tile_timeline(cfg, torch, hb, launches=4):
+    """Per-tile view of one launch of a carry-chained kernel (heinsen_set_timeline): where a tile's life
+    goes between its workgroup's start and its last store, and how the launch ramps up and drains.
+    Returns a text report (times in microseconds; the GPU's wall clock ticks at 100 MHz)."""
+    import numpy as np
+
+    a, b, x0, out = device_inputs(cfg, torch)
+    layout, flags = hb.LAYOUTS[cfg.layout], hb.flags_from_names(cfg.flags)
+    stream = torch.cuda.current_stream()
+    cap = 1 << 20
+    stamps = torch.zeros(cap * 8, dtype=torch.int64, device="cuda")
+    for _ in range(3):
+        hb.heinsen_scan(a, b, x0, out, cfg.B, cfg.D, cfg.n, layout, flags, stream)
+    torch.cuda.synchronize()
+    hb.heinsen_set_timeline(stamps, cap)
+    try:
+        for _ in range(launches):
+            stamps.zero_()
+            hb.heinsen_scan(a, b, x0, out, cfg.B, cfg.D, cfg.n, layout, flags, stream)
+            torch.cuda.synchronize()
+    finally:
+        hb.heinsen_set_timeline(None, 0)
+    t = stamps.cpu().numpy().reshape(cap, 8).astype(np.float64)
+    t = t[t[:, 7] > 0]
+    nt = t.shape[0]
+    t = (t - t[:, 0].min()) * 0.01
+    names = ["workgroup start -> ticket drawn", "ticket -> inputs loaded and scanned", "scanned -> summary handed on",
+             "summary -> carry records in", "records in -> start state known", "state -> outputs issued",
+             "outputs issued -> end"]
+    lines = [f"workload cfg{cfg.index} {cfg.shape()} {cfg.layout}: {nt} tiles stamped, kernel "
+             f"{hb.heinsen_kernel_name(cfg.B, cfg.D, cfg.n, layout, flags)}",
+             f"launch span (first workgroup start -> last tile end): {t[:, 7].max():.1f} us",
+             f"{'phase':46s} {'mean':>7s} {'p50':>7s} {'p90':>7s} {'max':>7s}"]
+    for i, nm in enumerate(names):
+        d = t[:, i + 1] - t[:, i]
+        lines.append(f"{nm:46s} {d.mean():7.2f} {np.median(d):7.2f} {np.percentile(d, 90):7.2f} {d.max():7.2f}")
+    life = t[:, 7] - t[:, 0]
+    lines.append(f"{'tile life (start -> end)':46s} {life.mean():7.2f} {np.median(life):7.2f} {np.percentile(life, 90):7.2f} {life.max():7.2f}")
+    starts, ends = np.sort(t[:, 0]), np.sort(t[:, 7])
+    resident = int(np.sum(starts <= starts[0] + 1e-9 + np.median(life) * 0.25))
+    k = min(nt - 1, 511)
+    lines.append(f"ramp: workgroup start of tile #1 at 0.0, #{k + 1} at {starts[k]:.1f} us; first ticket at {np.sort(t[:, 1])[0]:.1f}, "
+                 f"#{k + 1} ticket at {np.sort(t[:, 1])[k]:.1f} us  ({resident} workgroups started within a quarter of a tile life)")
+    lines.append(f"drain: last workgroup start at {starts[-1]:.1f} us, first tile end {ends[0]:.1f}, median end {np.median(ends):.1f}, "
+                 f"last end {ends[-1]:.1f} us -> {ends[-1] - starts[-1]:.1f} us with no new tile starting")
+    grid = np.linspace(0, ends[-1], 21)
+    alive = [int(np.sum((t[:, 0] <= g) & (t[:, 7] > g))) for g in grid]
+    lines.append("tiles alive at 5 % steps of the span: " + " ".join(str(v) for v in alive))
+    del a, b, x0, out, stamps
+    torch.cuda.empty_cache()
+    return "\n".join(lines)
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -181,6 +234,8 @@ def main() -> int:
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
     ap.add_argument("--fig1", action="store_true",
                     help="instead of the benchmark, run the paper's sequential-vs-parallel sweep over n (Fig. 1)")
+    ap.add_argument("--timeline", type=int, default=0, metavar="CFG",
+                    help="instead of the benchmark, print the per-tile timeline of one launch of configuration CFG (2, 3 or 5)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run plain device copies of a known size (reference for rocprofv3 FETCH_SIZE/WRITE_SIZE)")
     args = ap.parse_args()
@@ -202,6 +257,10 @@ def main() -> int:
     if args.fig1:
         print(json.dumps({"experiment": "time(sequential) / time(parallel) vs n, one sequence, one MI355X",
                           "runs_per_point": 30, "points": fig1_sweep(torch, hb)}))
+        return 0
+
+    if args.timeline:
+        print(tile_timeline(workloads.CONFIGS[args.timeline], torch, hb))
         return 0
 
     if args.copy_calibration:

@@ -67,8 +67,10 @@ typedef enum {
                                     scratch recorded into a graph on a stream that has none yet         */
     HEINSEN_ERR_ALLOC = 3,       /* scratch memory could not be allocated; nothing was launched          */
     HEINSEN_ERR_HIP = 4,         /* a HIP runtime call failed; see heinsen_last_hip_error()              */
-    HEINSEN_ERR_SCRATCH_LIMIT = 5 /* heinsen_scan_static only: the shape needs more scratch than its fixed
+    HEINSEN_ERR_SCRATCH_LIMIT = 5, /* heinsen_scan_static only: the shape needs more scratch than its fixed
                                     buffer holds; nothing was launched                                   */
+    HEINSEN_ERR_CARRY_LOST = 6   /* heinsen_check only: a tile gave up waiting for a carry record and wrote
+                                    NaN from there on (two launches used one scratch buffer at once)     */
 } heinsen_status_t;
 
 /*
@@ -92,22 +94,23 @@ typedef enum {
  * Asynchronous: work is enqueued on `stream` and the call returns without synchronising.  The
  * returned status covers argument validation, scratch allocation and launch errors only.
  *
- * Scratch: a grow-only buffer per (device, stream) holds the inter-tile carries.  It is allocated
- * with hipMalloc on the first call that needs it or needs more (that call synchronises the stream
- * if it replaces a buffer); later calls of the same or smaller shape allocate nothing.  Calls on
- * different streams never share scratch; calls on one stream may come from several host threads.
- * Carries of different launches are told apart by a launch counter.  For an ordinary call the host
- * keeps it.  A call that is being recorded into a HIP graph (stream capture) is replayed with the same
- * arguments many times and may not allocate: it uses the scratch its stream already has -- make one
- * ordinary call of at least the same shape on that stream first, as a warm-up does -- and records a
- * one-workgroup kernel in front of the scan that renews the counter in the scratch at every replay.
- * Without such scratch the call is refused with HEINSEN_ERR_UNSUPPORTED and nothing is recorded.
- * A graph keeps using the scratch it was recorded with (a later, larger ordinary call gets a new
- * buffer and the old one lives on until heinsen_release_scratch): its replays must not overlap with
- * one another or with ordinary calls on the stream it was recorded on, and heinsen_release_scratch
- * must not be called while the graph may still be replayed.  Shapes that need no carries (sequences
- * of at most 16384 steps in the [B, D, n] layout and of at most 64 steps in [B, n, D]) use no scratch
- * and may be captured without any of this.
+ * Scratch: a grow-only buffer per (device, stream) holds the inter-tile carries and the ticket queues
+ * that hand out the tiles.  It is allocated with hipMalloc on the first call that needs it or needs more
+ * (that call synchronises the stream if it replaces a buffer) and cleared by a small kernel on `stream`;
+ * later calls of the same or smaller shape allocate nothing.  Calls on different streams never share
+ * scratch; calls on one stream may come from several host threads.  Carries of different launches are
+ * told apart by a launch counter that lives in the buffer and is renewed by the kernels themselves, so the
+ * host keeps no per-launch state, a failed launch leaves nothing to repair, and a call recorded into a
+ * HIP graph (stream capture) replays like any other.  Such a call may not allocate, though: it uses the
+ * scratch its stream already has -- make one ordinary call of at least the same shape on that stream
+ * first, as a warm-up does -- and without it is refused with HEINSEN_ERR_UNSUPPORTED, nothing recorded.
+ * A graph keeps using the scratch it was recorded with (a later, larger ordinary call gets a new buffer
+ * and the old one lives on until heinsen_release_scratch): its replays must not overlap with one another
+ * or with ordinary calls on the stream it was recorded on, and heinsen_release_scratch must not be called
+ * while the graph may still be replayed.  Two launches that do use one buffer at the same time get wrong
+ * results but always end: a tile whose carry never arrives gives up after a few seconds of polling, writes
+ * NaN from there on and leaves a note that heinsen_check reports.  Shapes that need no carries (sequences
+ * of at most 16384 steps in the [B, D, n] layout and of at most 64 steps in [B, n, D]) use no scratch.
  *
  * Data-dependent conditions are not errors and follow IEEE arithmetic: a NaN input gives NaN from
  * that step on in that sequence only; a_t = 0 restarts the sequence at b_t; b_t = 0 and x_0 = 0 are
@@ -136,11 +139,21 @@ int heinsen_scan(const void *a_or_log_a, const void *b_or_log_b, const void *x0,
  *             the same time on one GPU race on it and give wrong results: keep them on one stream or
  *             order them with events.  heinsen_scan's own scratch is separate and never conflicts.
  *   capture : may be recorded into a HIP graph; the first call on a device looks up the array's address
- *             (hipGetSymbolAddress) and should be made outside a capture.
+ *             (hipGetSymbolAddress), clears it with a small kernel and synchronises `stream` once, and
+ *             must be made outside a capture (inside one it is refused with HEINSEN_ERR_UNSUPPORTED).
  * Returns a heinsen_status_t.
  */
 int heinsen_scan_static(const void *a_or_log_a, const void *b_or_log_b, const void *x0, void *out,
                         int64_t B, int64_t D, int64_t n, int layout, uint32_t flags, void *stream);
+
+/*
+ * heinsen_check -- synchronises `stream` and reports whether any launch since the last check gave up
+ * waiting for a carry record, in the scratch of (current device, stream) or in the fixed array of
+ * heinsen_scan_static on the current device.  Returns HEINSEN_OK, or HEINSEN_ERR_CARRY_LOST after
+ * putting the affected buffer back into its initial state (outputs written by the launches concerned
+ * hold NaN from the failing tile on).  Never needed in correct use; meant for debugging concurrency.
+ */
+int heinsen_check(void *stream);
 
 /* Static, NUL-terminated description of a heinsen_status_t value (never NULL). */
 const char *heinsen_status_string(int status);
@@ -170,6 +183,31 @@ int heinsen_kernel_name(int64_t B, int64_t D, int64_t n, int layout, uint32_t fl
  * Returns a heinsen_status_t.
  */
 int heinsen_sequential(const void *a, const void *b, const void *x0, void *out, int64_t n, void *stream);
+
+/*
+ * heinsen_set_timeline -- profiling aid (the per-tile view that a kernel-level profiler cannot give).
+ * While set, every tile of every later launch of the two carry-chained kernels writes eight 64-bit
+ * time stamps of the GPU's 100 MHz wall clock to stamps[tile * 8 + i], for tiles below `tiles`:
+ *   0 workgroup started, 1 ticket drawn (tile known), 2 inputs loaded and scanned in the lanes,
+ *   3 summary handed to the other waves, 4 carry records of the earlier tiles in, 5 start state known,
+ *   6 outputs issued, 7 end (all taken by the tile's first wave).
+ * Tile ids: [B, n, D]: chunk * columns + column; [B, D, n]: row-major.
+ * stamps: device memory, 8-byte aligned, tiles * 64 bytes, owned by the caller; (NULL, 0) switches the
+ * stamps off again (a launch without them pays one untaken branch per stamp).  Process-wide setting.
+ * Returns a heinsen_status_t.
+ */
+int heinsen_set_timeline(void *stamps, uint64_t tiles);
+
+/*
+ * heinsen_test_carry -- testing aid for the error path of the carry chain; not for production use.
+ *   spin_limit : polls after which a tile gives up waiting for a carry record (0 = the default, seconds);
+ *   drop_tile  : this tile id never publishes its summary, as if another launch had overwritten it
+ *                (0xffffffff = none);
+ *   epoch      : if non-zero, a small kernel on `stream` sets the launch counter of the stream's scratch
+ *                and of the fixed array to this value (1 .. 2^30 - 1), e.g. just before it comes round.
+ * Process-wide settings.  Every kernel still ends normally.  Returns a heinsen_status_t.
+ */
+int heinsen_test_carry(uint32_t spin_limit, uint32_t drop_tile, uint32_t epoch, void *stream);
 
 #ifdef __cplusplus
 }

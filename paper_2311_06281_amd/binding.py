@@ -33,9 +33,11 @@ HEINSEN_ERR_UNSUPPORTED = 2
 HEINSEN_ERR_ALLOC = 3
 HEINSEN_ERR_HIP = 4
 HEINSEN_ERR_SCRATCH_LIMIT = 5
+HEINSEN_ERR_CARRY_LOST = 6
 
 EXPORTS = ("heinsen_scan", "heinsen_scan_static", "heinsen_status_string", "heinsen_last_hip_error", "heinsen_version",
-           "heinsen_release_scratch", "heinsen_kernel_name", "heinsen_sequential")
+           "heinsen_release_scratch", "heinsen_kernel_name", "heinsen_sequential", "heinsen_check",
+           "heinsen_set_timeline", "heinsen_test_carry")
 
 _lib = None
 
@@ -68,6 +70,12 @@ def load() -> ctypes.CDLL:
         lib.heinsen_release_scratch.restype = ci
         lib.heinsen_kernel_name.argtypes = [i64, i64, i64, ci, u32, ctypes.c_char_p, ci]
         lib.heinsen_kernel_name.restype = ci
+        lib.heinsen_check.argtypes = [vp]
+        lib.heinsen_check.restype = ci
+        lib.heinsen_set_timeline.argtypes = [vp, ctypes.c_uint64]
+        lib.heinsen_set_timeline.restype = ci
+        lib.heinsen_test_carry.argtypes = [u32, u32, u32, vp]
+        lib.heinsen_test_carry.restype = ci
         lib.heinsen_sequential.argtypes = [vp, vp, vp, vp, i64, vp]
         lib.heinsen_sequential.restype = ci
         _lib = lib
@@ -154,6 +162,25 @@ def heinsen_scan_static(a, b, x0, out, B: int, D: int, n: int, layout: int, flag
         if st == HEINSEN_ERR_HIP:
             msg += f", hipError_t {heinsen_last_hip_error()}"
         raise HeinsenError(st, msg)
+
+
+def heinsen_check(stream=None) -> int:
+    """Synchronises `stream`; HEINSEN_OK, or HEINSEN_ERR_CARRY_LOST if a launch gave up waiting for a carry."""
+    return int(load().heinsen_check(_stream_handle(stream)))
+
+
+def heinsen_set_timeline(stamps, tiles: int) -> None:
+    """Per-tile time stamps into the device buffer `stamps` (tiles * 8 uint64); (None, 0) switches them off."""
+    st = int(load().heinsen_set_timeline(_addr(stamps), int(tiles)))
+    if st != HEINSEN_OK:
+        raise HeinsenError(st, heinsen_status_string(st))
+
+
+def heinsen_test_carry(spin_limit: int = 0, drop_tile: int = 0xFFFFFFFF, epoch: int = 0, stream=None) -> None:
+    """Testing aid of the carry chain's error path; see include/heinsen.h."""
+    st = int(load().heinsen_test_carry(int(spin_limit), int(drop_tile), int(epoch), _stream_handle(stream)))
+    if st != HEINSEN_OK:
+        raise HeinsenError(st, heinsen_status_string(st))
 
 
 def heinsen_sequential(a, b, x0, out, n: int, stream=None) -> None:

@@ -17,36 +17,34 @@ constexpr uint32_t kAllFlags =
 
 thread_local int t_last_hip_error = 0;
 
-// One buffer of tagged 64-bit records per (device, stream); see heinsen_internal.hpp.
+// One buffer of tagged 64-bit records per (device, stream); see heinsen_internal.hpp.  The host keeps no
+// counters for it: tickets and the launch counter live in the buffer's header and are renewed by the
+// kernels themselves.
 struct Scratch {
     unsigned long long *records = nullptr;
-    size_t capacity = 0;      // in records, including the header
-    uint32_t epoch = 0;       // epoch of the last ordinary launch (even; 0: none yet)
-    uint32_t ticket_base = 0; // value of the ticket counter when the next ordinary launch starts
+    size_t capacity = 0;      // in 64-bit words, including the header
     bool in_graph = false;    // a captured launch holds this buffer's address: it is not freed on growth
     std::vector<unsigned long long *> retired; // such buffers, replaced by larger ones; freed on release
 };
 
-// Recorded in front of every captured launch (one workgroup): gives the replay a fresh odd epoch and a
-// ticket counter at zero.  When the 30-bit epoch comes round, the records are cleared so that no tag of
-// an earlier cycle can match.
-__global__ void heinsen_graph_prologue(unsigned long long *records, size_t capacity)
+// Prepares a buffer for its first launch: all records cleared (no tag matches epoch 1), the ticket queues
+// at {epoch 1 | ticket 0}, the size noted for the launch that has to clear the records again when the
+// epochs come round.
+__global__ void heinsen_scratch_init(unsigned long long *scratch, size_t capacity)
 {
-    __shared__ uint32_t s_next, s_wrap;
-    if (threadIdx.x == 0) {
-        const uint32_t e = (uint32_t)records[hs::kHeaderGraphEpoch];
-        const uint32_t ne = e == 0 ? 1u : e + 2u;
-        s_wrap = ne >= (1u << 30) ? 1u : 0u;
-        s_next = s_wrap ? 1u : ne;
+    const size_t stride = (size_t)gridDim.x * blockDim.x;
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < capacity; i += stride) {
+        unsigned long long v = 0ull;
+        if (i < hs::kQueueStride * hs::kQueues && i % hs::kQueueStride == 0) v = 1ull << 32;
+        if (i == hs::kHeaderCapacity) v = (unsigned long long)capacity;
+        scratch[i] = v;
     }
-    __syncthreads();
-    if (s_wrap)
-        for (size_t i = hs::kRecordBase + threadIdx.x; i < capacity; i += blockDim.x) records[i] = 0;
-    __syncthreads();
-    if (threadIdx.x == 0) {
-        records[hs::kHeaderGraphTicket] = 0;
-        records[hs::kHeaderGraphEpoch] = s_next;
-    }
+}
+
+// Testing aid: puts the launch counter of a buffer at `epoch` (1 .. 2^30 - 1), e.g. just before it comes round.
+__global__ void heinsen_scratch_set_epoch(unsigned long long *scratch, uint32_t epoch)
+{
+    if (threadIdx.x < hs::kQueues) scratch[hs::kQueueStride * threadIdx.x] = (unsigned long long)epoch << 32;
 }
 
 std::mutex g_mutex;
@@ -59,6 +57,13 @@ constexpr size_t kStaticRecords = ((size_t)40 << 20) / sizeof(unsigned long long
 static __device__ __align__(256) unsigned long long scratch[kStaticRecords];
 constexpr int kMaxDevices = 64;
 unsigned long long *g_static_scratch[kMaxDevices] = {};
+
+// Settings of the carry waits and of the optional per-tile time stamps (process-wide, under g_mutex).
+constexpr uint32_t kDefaultSpinLimit = 1u << 22; // polls of about a microsecond each: seconds
+uint32_t g_spin_limit = kDefaultSpinLimit;
+uint32_t g_drop_tile = 0xffffffffu;
+unsigned long long *g_timeline = nullptr;
+uint32_t g_timeline_tiles = 0;
 
 bool hip_ok(hipError_t e)
 {
@@ -102,44 +107,77 @@ int describe(int64_t B, int64_t D, int64_t n, int layout, uint32_t flags, hs::Sc
     return HEINSEN_OK;
 }
 
-// Makes sure the stream's record buffer can hold `need`, and hands out the tag of the next launch.
-// Called with g_mutex held; the caller keeps it until the kernel is enqueued so that launches enter
-// the stream in epoch order.
-int prepare_launch(hipStream_t stream, const hs::ScratchNeed &need, Scratch *&out, hs::LaunchTag &tag)
+// Makes sure the stream's buffer holds at least `want` words.  Called with g_mutex held; the caller keeps
+// it until the kernel is enqueued.  While the stream is being captured nothing may be allocated: the call
+// then needs the buffer an earlier ordinary call of at least this size has made.
+int ensure_scratch(hipStream_t stream, size_t want, bool capturing, Scratch *&out)
 {
     int dev = 0;
     if (!hip_ok(hipGetDevice(&dev))) return HEINSEN_ERR_HIP;
-    Scratch &s = g_scratch[std::make_pair(dev, stream)];
-    const size_t want = hs::kRecordBase + need.records;
-    const bool wrap = s.epoch >= 0x3ffffffcu; // 30-bit epochs: start over on a cleared buffer
-    if (s.capacity < want || wrap) {
-        // work queued on the old buffer must drain before it is replaced or cleared
-        if (s.records && !hip_ok(hipStreamSynchronize(stream))) return HEINSEN_ERR_HIP;
-        if (s.capacity < want) {
-            if (s.records) {
-                if (s.in_graph) s.retired.push_back(s.records); // a graph may still replay into it
-                else (void)hipFree(s.records);
-            }
-            s.records = nullptr;
-            s.capacity = 0;
-            s.in_graph = false;
-            const size_t cap = hs::align_up(want + want / 2, 512);
-            void *ptr = nullptr;
-            if (!hip_ok(hipMalloc(&ptr, cap * sizeof(unsigned long long)))) return HEINSEN_ERR_ALLOC;
-            s.records = static_cast<unsigned long long *>(ptr);
-            s.capacity = cap;
-        }
-        if (!hip_ok(hipMemset(s.records, 0, s.capacity * sizeof(unsigned long long)))) return HEINSEN_ERR_HIP;
-        s.epoch = 0;
-        s.ticket_base = 0;
+    if (capturing) {
+        auto it = g_scratch.find(std::make_pair(dev, stream));
+        if (it == g_scratch.end() || it->second.capacity < want) return HEINSEN_ERR_UNSUPPORTED;
+        it->second.in_graph = true;
+        out = &it->second;
+        return HEINSEN_OK;
     }
-    s.epoch += 2; // even: launches replayed from graphs use the odd ones
-    tag.epoch = s.epoch;
-    tag.ticket_base = s.ticket_base;
-    tag.from_header = false;
-    s.ticket_base += need.tickets; // wraps modulo 2^32 together with the device counter
+    Scratch &s = g_scratch[std::make_pair(dev, stream)];
+    if (s.capacity < want) {
+        // work queued on the old buffer must drain before it is replaced
+        if (s.records && !hip_ok(hipStreamSynchronize(stream))) return HEINSEN_ERR_HIP;
+        if (s.records) {
+            if (s.in_graph) s.retired.push_back(s.records); // a graph may still replay into it
+            else (void)hipFree(s.records);
+        }
+        s.records = nullptr;
+        s.capacity = 0;
+        s.in_graph = false;
+        const size_t cap = hs::align_up(want + want / 2, 512);
+        void *ptr = nullptr;
+        if (!hip_ok(hipMalloc(&ptr, cap * sizeof(unsigned long long)))) return HEINSEN_ERR_ALLOC;
+        // cleared and armed on the call's own stream, ahead of the scan that is about to use it
+        hipLaunchKernelGGL(heinsen_scratch_init, dim3(1024), dim3(256), 0, stream, static_cast<unsigned long long *>(ptr), cap);
+        if (!hip_ok(hipGetLastError())) {
+            (void)hipFree(ptr);
+            return HEINSEN_ERR_HIP;
+        }
+        s.records = static_cast<unsigned long long *>(ptr);
+        s.capacity = cap;
+    }
     out = &s;
     return HEINSEN_OK;
+}
+
+// The fixed array of heinsen_scan_static on the current device (looked up and armed at the first call).
+int static_scratch(hipStream_t stream, bool capturing, unsigned long long *&out)
+{
+    int dev = 0;
+    if (!hip_ok(hipGetDevice(&dev))) return HEINSEN_ERR_HIP;
+    if (dev < 0 || dev >= kMaxDevices) return HEINSEN_ERR_UNSUPPORTED;
+    if (g_static_scratch[dev] == nullptr) {
+        if (capturing) return HEINSEN_ERR_UNSUPPORTED; // the first call on a device has to be an ordinary one
+        unsigned long long *ptr = nullptr;
+        if (!hip_ok(hipGetSymbolAddress(reinterpret_cast<void **>(&ptr), HIP_SYMBOL(scratch))) || ptr == nullptr)
+            return HEINSEN_ERR_HIP;
+        hipLaunchKernelGGL(heinsen_scratch_init, dim3(1024), dim3(256), 0, stream, ptr, kStaticRecords);
+        if (!hip_ok(hipGetLastError())) return HEINSEN_ERR_HIP;
+        // calls on other streams may follow: the array must be armed before any of them can run
+        if (!hip_ok(hipStreamSynchronize(stream))) return HEINSEN_ERR_HIP;
+        g_static_scratch[dev] = ptr;
+    }
+    out = g_static_scratch[dev];
+    return HEINSEN_OK;
+}
+
+hs::LaunchCtx make_ctx(unsigned long long *records)
+{
+    return hs::LaunchCtx{records, g_spin_limit, g_drop_tile, g_timeline, g_timeline_tiles};
+}
+
+bool is_capturing(hipStream_t stream)
+{
+    hipStreamCaptureStatus cap = hipStreamCaptureStatusNone;
+    return stream != nullptr && hipStreamIsCapturing(stream, &cap) == hipSuccess && cap != hipStreamCaptureStatusNone;
 }
 
 // Checks the arguments of a scan call and fills `c`; `bnd` tells which layout path serves it.
@@ -174,38 +212,20 @@ int heinsen_scan(const void *a, const void *b, const void *x0, void *out, int64_
     if (st != HEINSEN_OK) return st;
 
     const hs::ScratchNeed need = bnd ? hs::bnd_scratch(c) : hs::bdn_scratch(c);
-    if (need.records == 0 && need.tickets == 0) {
-        hipError_t e = bnd ? hs::bnd_launch(c, nullptr, hs::LaunchTag{0, 0, false}) : hs::bdn_launch(c, nullptr, hs::LaunchTag{0, 0, false});
-        return hip_ok(e) ? HEINSEN_OK : HEINSEN_ERR_HIP;
-    }
-    // The carry records are told apart by a per-launch epoch.  An ordinary launch gets it from the host;
-    // a launch that is recorded once and replayed many times (HIP graph capture) cannot, and nothing may
-    // be allocated while a stream is capturing: such a call uses the scratch the stream already has (an
-    // earlier ordinary call of at least this size made it) and takes epoch and tickets from its header,
-    // which a small kernel recorded in front of it renews at every replay.
-    hipStreamCaptureStatus cap = hipStreamCaptureStatusNone;
-    if (c.stream != nullptr && hipStreamIsCapturing(c.stream, &cap) == hipSuccess && cap != hipStreamCaptureStatusNone) {
-        std::lock_guard<std::mutex> lock(g_mutex);
-        int dev = 0;
-        if (!hip_ok(hipGetDevice(&dev))) return HEINSEN_ERR_HIP;
-        auto it = g_scratch.find(std::make_pair(dev, c.stream));
-        if (it == g_scratch.end() || it->second.capacity < hs::kRecordBase + need.records) return HEINSEN_ERR_UNSUPPORTED;
-        Scratch &sc = it->second;
-        sc.in_graph = true;
-        hipLaunchKernelGGL(heinsen_graph_prologue, dim3(1), dim3(256), 0, c.stream, sc.records, sc.capacity);
-        if (!hip_ok(hipGetLastError())) return HEINSEN_ERR_HIP;
-        const hs::LaunchTag gtag{0, 0, true};
-        hipError_t e = bnd ? hs::bnd_launch(c, sc.records, gtag) : hs::bdn_launch(c, sc.records, gtag);
-        return hip_ok(e) ? HEINSEN_OK : HEINSEN_ERR_HIP;
-    }
     std::lock_guard<std::mutex> lock(g_mutex);
-    Scratch *s = nullptr;
-    hs::LaunchTag tag{0, 0, false};
-    st = prepare_launch(c.stream, need, s, tag);
-    if (st != HEINSEN_OK) return st;
-    hipError_t e = bnd ? hs::bnd_launch(c, s->records, tag) : hs::bdn_launch(c, s->records, tag);
-    if (!hip_ok(e)) return HEINSEN_ERR_HIP;
-    return HEINSEN_OK;
+    unsigned long long *records = nullptr;
+    if (need.records != 0) {
+        // A call recorded into a HIP graph is replayed with the same arguments many times and may not
+        // allocate: it uses the buffer the stream already has.  Nothing else is special about it -- the
+        // kernels keep tickets and launch counter in the buffer themselves.
+        Scratch *sc = nullptr;
+        st = ensure_scratch(c.stream, hs::kRecordBase + need.records, is_capturing(c.stream), sc);
+        if (st != HEINSEN_OK) return st;
+        records = sc->records;
+    }
+    const hs::LaunchCtx ctx = make_ctx(records);
+    const hipError_t e = bnd ? hs::bnd_launch(c, ctx) : hs::bdn_launch(c, ctx);
+    return hip_ok(e) ? HEINSEN_OK : HEINSEN_ERR_HIP;
 }
 
 int heinsen_scan_static(const void *a, const void *b, const void *x0, void *out, int64_t B, int64_t D, int64_t n,
@@ -216,30 +236,80 @@ int heinsen_scan_static(const void *a, const void *b, const void *x0, void *out,
     int st = make_call(a, b, x0, out, B, D, n, layout, flags, stream, c, bnd);
     if (st != HEINSEN_OK) return st;
     const hs::ScratchNeed need = bnd ? hs::bnd_scratch(c) : hs::bdn_scratch(c);
-    if (need.records == 0 && need.tickets == 0) {
-        hipError_t e = bnd ? hs::bnd_launch(c, nullptr, hs::LaunchTag{0, 0, false}) : hs::bdn_launch(c, nullptr, hs::LaunchTag{0, 0, false});
-        return hip_ok(e) ? HEINSEN_OK : HEINSEN_ERR_HIP;
+    if (need.records != 0 && hs::kRecordBase + need.records > kStaticRecords) return HEINSEN_ERR_SCRATCH_LIMIT;
+    std::lock_guard<std::mutex> lock(g_mutex);
+    unsigned long long *records = nullptr;
+    if (need.records != 0) {
+        // The array keeps whatever the last call left in it.  Nothing has to be cleared: every launch finds
+        // in the header a launch counter that no record in the array carries yet.
+        st = static_scratch(c.stream, is_capturing(c.stream), records);
+        if (st != HEINSEN_OK) return st;
     }
-    if (hs::kRecordBase + need.records > kStaticRecords) return HEINSEN_ERR_SCRATCH_LIMIT;
+    const hs::LaunchCtx ctx = make_ctx(records);
+    const hipError_t e = bnd ? hs::bnd_launch(c, ctx) : hs::bdn_launch(c, ctx);
+    return hip_ok(e) ? HEINSEN_OK : HEINSEN_ERR_HIP;
+}
+
+int heinsen_check(void *stream_)
+{
+    hipStream_t stream = static_cast<hipStream_t>(stream_);
     std::lock_guard<std::mutex> lock(g_mutex);
     int dev = 0;
     if (!hip_ok(hipGetDevice(&dev))) return HEINSEN_ERR_HIP;
-    if (dev < 0 || dev >= kMaxDevices) return HEINSEN_ERR_UNSUPPORTED;
-    if (g_static_scratch[dev] == nullptr) {
-        unsigned long long *ptr = nullptr;
-        if (!hip_ok(hipGetSymbolAddress(reinterpret_cast<void **>(&ptr), HIP_SYMBOL(scratch))) || ptr == nullptr)
-            return HEINSEN_ERR_HIP;
-        g_static_scratch[dev] = ptr;
+    if (!hip_ok(hipStreamSynchronize(stream))) return HEINSEN_ERR_HIP;
+    unsigned long long *bufs[2] = {nullptr, nullptr};
+    size_t caps[2] = {0, 0};
+    auto it = g_scratch.find(std::make_pair(dev, stream));
+    if (it != g_scratch.end()) {
+        bufs[0] = it->second.records;
+        caps[0] = it->second.capacity;
     }
-    unsigned long long *records = g_static_scratch[dev];
-    // The array keeps whatever the last call left in it.  Nothing has to be cleared: the one-workgroup
-    // kernel in front of the scan gives this call a launch counter no record in the array carries yet and
-    // a ticket counter at zero (and clears the records itself when the counter comes round).
-    hipLaunchKernelGGL(heinsen_graph_prologue, dim3(1), dim3(256), 0, c.stream, records, kStaticRecords);
-    if (!hip_ok(hipGetLastError())) return HEINSEN_ERR_HIP;
-    const hs::LaunchTag tag{0, 0, true};
-    hipError_t e = bnd ? hs::bnd_launch(c, records, tag) : hs::bdn_launch(c, records, tag);
-    return hip_ok(e) ? HEINSEN_OK : HEINSEN_ERR_HIP;
+    if (dev >= 0 && dev < kMaxDevices) {
+        bufs[1] = g_static_scratch[dev];
+        caps[1] = kStaticRecords;
+    }
+    int status = HEINSEN_OK;
+    for (int i = 0; i < 2; ++i) {
+        if (bufs[i] == nullptr) continue;
+        unsigned long long err = 0;
+        if (!hip_ok(hipMemcpy(&err, bufs[i] + hs::kHeaderError, sizeof(err), hipMemcpyDeviceToHost))) return HEINSEN_ERR_HIP;
+        if (err == 0) continue;
+        status = HEINSEN_ERR_CARRY_LOST;
+        // tickets and records may be in any state after two launches have shared the buffer: start it afresh
+        hipLaunchKernelGGL(heinsen_scratch_init, dim3(1024), dim3(256), 0, stream, bufs[i], caps[i]);
+        if (!hip_ok(hipGetLastError()) || !hip_ok(hipStreamSynchronize(stream))) return HEINSEN_ERR_HIP;
+    }
+    return status;
+}
+
+int heinsen_set_timeline(void *stamps, uint64_t tiles)
+{
+    if ((stamps == nullptr) != (tiles == 0) || tiles > 0xffffffffull || reinterpret_cast<uintptr_t>(stamps) % 8)
+        return HEINSEN_ERR_INVALID_ARG;
+    std::lock_guard<std::mutex> lock(g_mutex);
+    g_timeline = static_cast<unsigned long long *>(stamps);
+    g_timeline_tiles = (uint32_t)tiles;
+    return HEINSEN_OK;
+}
+
+int heinsen_test_carry(uint32_t spin_limit, uint32_t drop_tile, uint32_t epoch, void *stream_)
+{
+    hipStream_t stream = static_cast<hipStream_t>(stream_);
+    if (epoch > hs::kLastEpoch) return HEINSEN_ERR_INVALID_ARG;
+    std::lock_guard<std::mutex> lock(g_mutex);
+    g_spin_limit = spin_limit == 0 ? kDefaultSpinLimit : spin_limit;
+    g_drop_tile = drop_tile;
+    if (epoch != 0) {
+        int dev = 0;
+        if (!hip_ok(hipGetDevice(&dev))) return HEINSEN_ERR_HIP;
+        auto it = g_scratch.find(std::make_pair(dev, stream));
+        if (it != g_scratch.end() && it->second.records != nullptr)
+            hipLaunchKernelGGL(heinsen_scratch_set_epoch, dim3(1), dim3(64), 0, stream, it->second.records, epoch);
+        if (dev >= 0 && dev < kMaxDevices && g_static_scratch[dev] != nullptr)
+            hipLaunchKernelGGL(heinsen_scratch_set_epoch, dim3(1), dim3(64), 0, stream, g_static_scratch[dev], epoch);
+        if (!hip_ok(hipGetLastError())) return HEINSEN_ERR_HIP;
+    }
+    return HEINSEN_OK;
 }
 
 const char *heinsen_status_string(int status)
@@ -250,6 +320,7 @@ const char *heinsen_status_string(int status)
     case HEINSEN_ERR_UNSUPPORTED: return "unsupported combination of arguments";
     case HEINSEN_ERR_ALLOC: return "scratch allocation failed";
     case HEINSEN_ERR_HIP: return "HIP runtime error";
+    case HEINSEN_ERR_CARRY_LOST: return "a tile gave up waiting for a carry record (two launches shared one scratch buffer?)";
     case HEINSEN_ERR_SCRATCH_LIMIT: return "the call needs more scratch than the fixed buffer of heinsen_scan_static holds";
     default: return "unknown status";
     }
@@ -257,7 +328,7 @@ const char *heinsen_status_string(int status)
 
 int heinsen_last_hip_error(void) { return t_last_hip_error; }
 
-int heinsen_version(void) { return 200; /* 0.2.0: OUT_COMPLEX, LINEAR */ }
+int heinsen_version(void) { return 300; /* 0.3.0: heinsen_scan_static, heinsen_check, heinsen_set_timeline */ }
 
 int heinsen_release_scratch(void)
 {

@@ -21,37 +21,48 @@ struct ScanCall {
     hipStream_t stream;
 };
 
-// Scratch is one buffer of 64-bit tagged records per (device, stream) (see heinsen_math.hpp).  Header
-// words: 0 = ticket counter of ordinary launches, 1 = ticket counter and 16 = epoch of launches replayed
-// from a HIP graph; carry records start at kRecordBase.  (The epoch, which every workgroup reads, has a
-// 128-byte line of its own: on the line of a ticket counter its readers would queue with the atomics.)
-// Every launch gets a fresh epoch, so the buffer never needs clearing.  An ordinary launch gets its
-// epoch (even) and `ticket_base`, the value word 0 has when the launch starts, from the host, which
-// adds the tickets drawn after every launch.  A launch recorded into a graph cannot: the same kernel
-// arguments are replayed many times.  It reads its epoch (odd) from word 16 and draws tickets from
-// word 1, both set by a one-workgroup kernel recorded in front of it (heinsen_api.hip), and leaves
-// word 0 and the host's copy of it alone.
-constexpr size_t kRecordBase = 32;
-constexpr size_t kHeaderGraphTicket = 1, kHeaderGraphEpoch = 16;
+// Scratch is one buffer of 64-bit words: a header, then the tagged carry records (see heinsen_math.hpp).
+//
+// Header.  Words 16*q, q = 0..7, are the ticket queues, each on a 128-byte line of its own.  A queue word is
+// {launch counter ("epoch"): high 32 bits | next ticket: low 32 bits}: one fetch-add hands a workgroup its
+// tile and the epoch its carry records are tagged with.  A launch draws a fixed number of tickets from
+// each queue it uses (its grid size over the number of queues); the workgroup that draws the last ticket
+// of a queue knows that nobody will draw from it again in this launch, and the one that completes the last
+// queue (kHeaderQueuesDone counts them) rewrites all eight queue words to {epoch + 1 | 0}.  So every launch,
+// ordinary or replayed from a HIP graph, finds the queues at zero with an epoch no record carries yet,
+// without any bookkeeping on the host and without anything to undo when a launch fails.  Epochs run
+// 1 .. 2^30 - 1; the launch that has the last one clears the records when its last workgroup ends.
+// Other header words: the buffer's size, an error word (a carry wait that gave up), and the two counters
+// just named.  Records start at kRecordBase.
+constexpr size_t kRecordBase = 256;
+constexpr int kQueues = 8;                 // one per compute die
+constexpr size_t kQueueStride = 16;        // words between queue counters (128 bytes)
+constexpr size_t kHeaderCapacity = 128;    // size of the buffer in words, header included
+constexpr size_t kHeaderError = 129;       // non-zero: some tile gave up waiting for a carry record
+constexpr size_t kHeaderQueuesDone = 144;  // queues of the current launch that have handed out all their tickets
+constexpr size_t kHeaderExited = 160;      // workgroups that have ended (counted only by the launch that clears)
+constexpr uint32_t kLastEpoch = (1u << 30) - 1u;
 
-struct LaunchTag {
-    uint32_t epoch;       // 2, 4, .. 2^30 - 2 (ignored when from_header)
-    uint32_t ticket_base; // ticket counter value at launch (ignored when from_header)
-    bool from_header;     // launch recorded into a graph: epoch and tickets come from the header
+// What the host tells a launch that uses carry records.
+struct LaunchCtx {
+    unsigned long long *scratch;   // header + records; null when the launch needs no carries
+    uint32_t spin_limit;           // polls after which a tile gives up waiting for a carry record
+    uint32_t drop_tile;            // testing aid: this tile never publishes its summary (0xffffffff: none)
+    unsigned long long *timeline;  // optional [timeline_tiles][8] wall-clock stamps per tile, or null
+    uint32_t timeline_tiles;
 };
 
-// Each path reports how many records it needs beyond kRecordBase (may be 0) and how many tickets a
-// launch draws, launches on call.stream, and names the kernel it would launch.
+// Each path reports how many records it needs beyond kRecordBase (may be 0), launches on call.stream, and
+// names the kernel it would launch.
 struct ScratchNeed {
     size_t records;
-    uint32_t tickets;
 };
 ScratchNeed bnd_scratch(const ScanCall &c);
-hipError_t bnd_launch(const ScanCall &c, unsigned long long *records, LaunchTag tag);
+hipError_t bnd_launch(const ScanCall &c, const LaunchCtx &ctx);
 const char *bnd_kernel_name(const ScanCall &c);
 
 ScratchNeed bdn_scratch(const ScanCall &c);
-hipError_t bdn_launch(const ScanCall &c, unsigned long long *records, LaunchTag tag);
+hipError_t bdn_launch(const ScanCall &c, const LaunchCtx &ctx);
 const char *bdn_kernel_name(const ScanCall &c);
 
 static inline int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }

@@ -16,12 +16,9 @@
 // arithmetic is in heinsen_math.hpp.
 #include "heinsen_internal.hpp"
 #include "heinsen_math.hpp"
-#include <cstdlib>
+#include "heinsen_tickets.hpp"
 
 namespace hs {
-#ifdef HS_TRACE
-extern unsigned long long *g_trace_bdn_storage;
-#endif
 namespace {
 
 // ---- lane-level pieces shared by the kernels ----------------------------------------------------------
@@ -488,28 +485,13 @@ struct TileParams {
     int x0_stride;
     uint32_t tpr;          // tiles per row
     uint32_t ntiles;       // rows * tpr
-    uint32_t epoch;
-    uint32_t ticket_base;
-    int from_header; // replayed from a graph: epoch and tickets come from the scratch header
-    rec_t *ticket;
+    rec_t *header;         // scratch header (ticket queue 0 hands out the tiles in row-major order)
     rec_t *recs;           // per row: level-1 and level-2 summaries (2 records each), states (2 records each)
     uint32_t off2, off4, row_stride; // record offsets of level 2 and of the states inside a row's block
-#ifdef HS_TRACE
-    unsigned long long *trace;
-#endif
+    uint32_t spin_limit;
+    uint32_t drop_tile;
+    Timeline tl;
 };
-
-#ifdef HS_TRACE
-#define HS_STAMP(i)                                                              \
-    do {                                                                         \
-        if (threadIdx.x == 0) p.trace[(size_t)tile * 8 + (i)] = wall_clock64(); \
-    } while (0)
-#define g_trace_bdn ::hs::g_trace_bdn_storage
-#else
-#define HS_STAMP(i) \
-    do {            \
-    } while (0)
-#endif
 
 struct State64 {
     double lx;
@@ -541,14 +523,12 @@ __device__ __forceinline__ State64 seg_apply64(const State64 &x, const Seg &g)
 }
 
 template <int DOM, bool LOG_IN, bool LOG_OUT, typename InT, bool VECIO, bool MULTI, int ITEMS>
-__global__ __launch_bounds__(kTileWaves * 64) void heinsen_scan_tiles(TileParams p)
+__device__ __forceinline__ void tiles_tile(const TileParams &p, const uint32_t tile, const uint32_t epoch)
 {
     constexpr bool SIGNED = DOM == kSigned;
     constexpr int NW = kTileWaves;
     constexpr int kTile = NW * 64 * ITEMS; // elements per tile
     static_assert(!MULTI || ITEMS == kTileItems, "rows of several tiles use the full tile");
-    __shared__ uint32_t s_tile;
-    __shared__ uint32_t s_epoch;
     __shared__ float lds_A[NW], lds_M[NW];
     __shared__ uint32_t lds_S[NW];
     __shared__ float lds_startL;
@@ -557,24 +537,6 @@ __global__ __launch_bounds__(kTileWaves * 64) void heinsen_scan_tiles(TileParams
     const int lane = threadIdx.x & 63;
     const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
 
-    uint32_t tile = blockIdx.x;
-    if (MULTI) {
-        // tickets: a tile only ever waits for tiles with smaller tickets, which are already running
-        if (threadIdx.x == 0) {
-            uint32_t *counter = reinterpret_cast<uint32_t *>(p.ticket + (p.from_header ? kHeaderGraphTicket : 0));
-            s_tile = __hip_atomic_fetch_add(counter, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) -
-                     (p.from_header ? 0u : p.ticket_base);
-            // a replayed launch finds its epoch in the header (written by the kernel recorded before this one)
-            s_epoch = p.from_header ? (uint32_t)p.ticket[kHeaderGraphEpoch] : p.epoch;
-        }
-        __syncthreads();
-        tile = __builtin_amdgcn_readfirstlane(s_tile);
-        // a ticket outside the launch means the counter and the host's record of it have come apart
-        // (an earlier launch on this stream died): touch nothing rather than index out of bounds
-        if (tile >= p.ntiles) return;
-    }
-    const uint32_t epoch = MULTI ? (uint32_t)__builtin_amdgcn_readfirstlane((int)s_epoch) : 0u;
-    HS_STAMP(0);
     const int64_t row = tile / p.tpr;
     const uint32_t c = tile % p.tpr;
     const InT *arow = reinterpret_cast<const InT *>(p.a) + row * p.n;
@@ -634,7 +596,7 @@ __global__ __launch_bounds__(kTileWaves * 64) void heinsen_scan_tiles(TileParams
     Seg mine = lane_scan<DOM, LOG_IN, LOG_OUT, ITEMS>(Av, Mv, sw, sm);
     Seg incl = wave_inclusive_scan<DOM>(mine);
     Seg lane_excl = wave_shift_up<DOM>(incl);
-    HS_STAMP(1);
+    p.tl.mark(tile, 2);
     if (lane == 63) {
         lds_A[w] = incl.A;
         lds_M[w] = incl.M;
@@ -663,18 +625,28 @@ __global__ __launch_bounds__(kTileWaves * 64) void heinsen_scan_tiles(TileParams
             encode<DOM, LOG_IN>(p.x0[p.x0_stride ? row : 0], lx, st.s);
             st.lx = (double)lx;
         }
-        HS_STAMP(2);
+        p.tl.mark(tile, 3);
         if (MULTI) {
-            if (more && r < 31u && lane == 0) seg_put<DOM>(rrow + kRecStride * (size_t)c, rrow + kRecStride * (size_t)c + 1, total, epoch);
+            if (more && r < 31u && lane == 0 && tile != p.drop_tile)
+                seg_put<DOM>(rrow + kRecStride * (size_t)c, rrow + kRecStride * (size_t)c + 1, total, epoch);
             // The last tile of a group owes the later groups the summary of its group; it needs level 1
             // only and is published as soon as that is in, whatever else is still on its way.
             const bool lead = more && r == 31u;
             bool pub2 = !lead;
             Seg f1 = seg_identity<DOM>(), f2 = seg_identity<DOM>(), a2 = seg_identity<DOM>();
             const uint64_t m1 = 0x7fffffff00000000ull, all = ~0ull;
+            bool lost = false; // some record never came
+            uint32_t polls = 0;
             for (;;) {
+                if (!lost && have != all && ++polls > p.spin_limit) {
+                    // give up: go on as if everything were in, with NaN as the state, which is also handed on
+                    lost = true;
+                    have = all;
+                    if (lane == 0) note_wait_gave_up(p.header);
+                }
                 if ((!pub2 && (have & m1) == m1) || have == all) {
                     Seg part = (need && got && lane != 31) ? seg_from<DOM>(ra, rm) : seg_identity<DOM>();
+                    if (lost) part.M = __builtin_nanf("");
                     part = half_inclusive_scan<DOM>(part);
                     f2 = seg_readlane<DOM>(part, 31);
                     f1 = seg_readlane<DOM>(part, 63);
@@ -689,7 +661,7 @@ __global__ __launch_bounds__(kTileWaves * 64) void heinsen_scan_tiles(TileParams
                 __builtin_amdgcn_s_sleep(2);
                 have = fetch_records();
             }
-            HS_STAMP(3);
+            p.tl.mark(tile, 4);
             if (sb > 0) {
                 // lane 31 holds the super-block state: payloads are the high and low word of the double,
                 // the sign rides in the user bits of the first record
@@ -699,6 +671,7 @@ __global__ __launch_bounds__(kTileWaves * 64) void heinsen_scan_tiles(TileParams
                 st.lx = __longlong_as_double((long long)(((unsigned long long)hi << 32) | lo));
                 st.s = SIGNED ? (sg << 31) : 0u;
             }
+            if (lost) st.lx = __builtin_nan("");
             const State64 st2 = seg_apply64<DOM>(st, f2); // state at the start of the group
             if (lead && g == 31u) {
                 const State64 nx = seg_apply64<DOM>(st2, a2); // start of the next super-block
@@ -710,7 +683,6 @@ __global__ __launch_bounds__(kTileWaves * 64) void heinsen_scan_tiles(TileParams
             }
             st = seg_apply64<DOM>(st2, f1);
         }
-        HS_STAMP(4);
         if (lane == 0) {
             lds_startL = (float)st.lx;
             lds_startS = st.s;
@@ -718,7 +690,7 @@ __global__ __launch_bounds__(kTileWaves * 64) void heinsen_scan_tiles(TileParams
     }
     __syncthreads();
 
-    HS_STAMP(5);
+    p.tl.mark(tile, 5);
     State st;
     st.lx = lds_startL;
     st.s = lds_startS;
@@ -743,8 +715,33 @@ __global__ __launch_bounds__(kTileWaves * 64) void heinsen_scan_tiles(TileParams
         wave_emit_blocked_elems<DOM, LOG_OUT, ITEMS>(orow + OW * wstart, p.n - wstart, reinterpret_cast<uint32_t *>(stage[w]), lane,
                                                      st, Av, Mv, sw, sm);
     }
-    HS_STAMP(6);
-    HS_STAMP(7);
+    p.tl.mark(tile, 6);
+}
+
+template <int DOM, bool LOG_IN, bool LOG_OUT, typename InT, bool VECIO, bool MULTI, int ITEMS>
+__global__ __launch_bounds__(kTileWaves * 64) void heinsen_scan_tiles(TileParams p)
+{
+    __shared__ uint32_t s_tile, s_epoch, s_flag;
+    const unsigned long long t_begin = p.tl.stamps != nullptr ? wall_clock64() : 0ull;
+    uint32_t tile = blockIdx.x, epoch = 0u;
+    if (MULTI) {
+        // tickets: a tile only ever waits for tiles with smaller tickets, which are already running
+        if (threadIdx.x == 0) {
+            const Draw d = draw_ticket(p.header, 0, p.ntiles, 1);
+            s_tile = d.ticket;
+            s_epoch = d.epoch;
+        }
+        __syncthreads();
+        tile = (uint32_t)__builtin_amdgcn_readfirstlane((int)s_tile);
+        epoch = (uint32_t)__builtin_amdgcn_readfirstlane((int)s_epoch);
+    }
+    if (tile < p.ntiles) {
+        p.tl.mark_at(tile, 0, t_begin);
+        p.tl.mark(tile, 1);
+        tiles_tile<DOM, LOG_IN, LOG_OUT, InT, VECIO, MULTI, ITEMS>(p, tile, epoch);
+        p.tl.mark(tile, 7);
+    }
+    if (MULTI) end_of_workgroup(p.header, epoch, &s_flag);
 }
 
 // ---- host side -------------------------------------------------------------------------------------------
@@ -798,7 +795,7 @@ BdnPlan make_plan(const ScanCall &c)
 }
 
 template <int DOM, bool LOG_IN, bool LOG_OUT, typename InT>
-hipError_t launch_mode(const ScanCall &c, const BdnPlan &pl, rec_t *records, LaunchTag tag)
+hipError_t launch_mode(const ScanCall &c, const BdnPlan &pl, const LaunchCtx &ctx)
 {
     if (pl.wave_kernel && pl.group > 0) {
         PackedParams p;
@@ -853,18 +850,17 @@ hipError_t launch_mode(const ScanCall &c, const BdnPlan &pl, rec_t *records, Lau
     p.x0_stride = c.x0_scalar ? 0 : 1;
     p.tpr = pl.tpr;
     p.ntiles = pl.ntiles;
-    p.epoch = tag.epoch;
-    p.ticket_base = tag.ticket_base;
-    p.from_header = tag.from_header ? 1 : 0;
-    p.ticket = records;
+    rec_t *records = pl.multi ? ctx.scratch : nullptr;
+    if (pl.multi && records == nullptr) return hipErrorInvalidValue;
+    p.header = records;
     p.recs = records ? records + kRecordBase : nullptr;
+    p.spin_limit = ctx.spin_limit;
+    p.drop_tile = ctx.drop_tile;
+    p.tl.stamps = ctx.timeline;
+    p.tl.tiles = ctx.timeline_tiles;
     p.off2 = pl.off2;
     p.off4 = pl.off4;
     p.row_stride = pl.row_stride;
-#ifdef HS_TRACE
-    if (!g_trace_bdn) (void)hipMalloc(&g_trace_bdn, (size_t)(1u << 20) * 8 * sizeof(unsigned long long));
-    p.trace = g_trace_bdn;
-#endif
     dim3 grid(pl.ntiles), block(kTileWaves * 64);
 #define HS_TILES(VEC_, MULTI_, ITEMS_) \
     hipLaunchKernelGGL((heinsen_scan_tiles<DOM, LOG_IN, LOG_OUT, InT, VEC_, MULTI_, ITEMS_>), grid, block, 0, c.stream, p)
@@ -885,9 +881,9 @@ hipError_t launch_mode(const ScanCall &c, const BdnPlan &pl, rec_t *records, Lau
     return hipGetLastError();
 }
 
-hipError_t launch_dispatch(const ScanCall &c, const BdnPlan &pl, rec_t *records, LaunchTag tag)
+hipError_t launch_dispatch(const ScanCall &c, const BdnPlan &pl, const LaunchCtx &ctx)
 {
-    HS_DISPATCH_MODE(c, launch_mode, c, pl, records, tag);
+    HS_DISPATCH_MODE(c, launch_mode, c, pl, ctx);
 }
 
 } // namespace
@@ -895,23 +891,15 @@ hipError_t launch_dispatch(const ScanCall &c, const BdnPlan &pl, rec_t *records,
 ScratchNeed bdn_scratch(const ScanCall &c)
 {
     BdnPlan pl = make_plan(c);
-    return ScratchNeed{pl.records, pl.multi ? pl.ntiles : 0u};
+    return ScratchNeed{pl.records};
 }
 
-hipError_t bdn_launch(const ScanCall &c, unsigned long long *records, LaunchTag tag)
+hipError_t bdn_launch(const ScanCall &c, const LaunchCtx &ctx)
 {
     BdnPlan pl = make_plan(c);
-    return launch_dispatch(c, pl, records, tag);
+    return launch_dispatch(c, pl, ctx);
 }
 
-#ifdef HS_TRACE
-namespace { }
-unsigned long long *g_trace_bdn_storage = nullptr;
-extern "C" int heinsen_debug_trace_bdn(unsigned long long *host, size_t ntiles)
-{
-    return (int)hipMemcpy(host, g_trace_bdn_storage, ntiles * 8 * sizeof(unsigned long long), hipMemcpyDeviceToHost);
-}
-#endif
 
 const char *bdn_kernel_name(const ScanCall &c)
 {

@@ -36,7 +36,7 @@ def test_header_constants_match_binding():
 
 def test_version_and_status_strings():
     assert hb.heinsen_version() >= 100
-    for st in range(0, 6):
+    for st in range(0, 7):
         assert hb.heinsen_status_string(st) not in ("", "unknown status")
     assert hb.heinsen_status_string(99) == "unknown status"
 
