@@ -124,17 +124,19 @@ int heinsen_scan(const void *a_or_log_a, const void *b_or_log_b, const void *x0,
 
 /*
  * heinsen_scan_static -- heinsen_scan for callers that cannot allocate device memory: code under HIP
- * graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments, same kernels, same
- * results bit for bit.  It never calls hipMalloc, hipFree or any allocating routine: the inter-tile
- * carries live in a fixed 40 MiB device array that is part of the library (each GPU the library runs on
- * holds its own copy until the process ends).
+ * graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments, same kernels.  It
+ * never calls hipMalloc, hipFree or any allocating routine: the inter-tile carries live in a fixed
+ * 48 MiB device array that is part of the library (each GPU the library runs on holds its own copy
+ * until the process ends).  Results are those of heinsen_scan bit for bit, except for large [B, n, D]
+ * shapes whose preferred (wider) tiles would not fit the array: those run with the narrower tiles, whose
+ * float32 rounding differs in the last bits.
  *
  *   limit   : shapes whose carries do not fit are refused with HEINSEN_ERR_SCRATCH_LIMIT and nothing is
- *             launched.  In records of 8 bytes, 32 + the following must stay within 5 * 2^20:
- *               [B, n, D], n > 64 : about 128 * ceil(D/64) * B * ceil(n/256) * 1.125
+ *             launched.  In records of 8 bytes, 256 + the following must stay within 6 * 2^20:
+ *               [B, n, D], n > 64 : about 160 * ceil(D/64) * B * ceil(n/256)
  *               [B, D, n], n > 16384 : about 16 * B * D * ceil(n/16384) * 1.04
- *             (all five benchmark shapes fit; [16, 16384, 2048] float32 takes 36 MiB.)  Shapes that need
- *             no carries have no limit.
+ *             (all five benchmark shapes fit; [16, 16384, 2048] float32 takes 40 of the 48 MiB.)  Shapes
+ *             that need no carries have no limit.
  *   sharing : every call on a GPU uses that GPU's one array, whatever the stream.  Calls that may run at
  *             the same time on one GPU race on it and give wrong results: keep them on one stream or
  *             order them with events.  heinsen_scan's own scratch is separate and never conflicts.

@@ -53,7 +53,7 @@ std::map<std::pair<int, hipStream_t>, Scratch> g_scratch;
 // Scratch of heinsen_scan_static: one fixed array per GPU, part of the loaded code, never allocated or
 // freed.  In host code the array's name is not a device address; the address on each device is looked
 // up once (hipGetSymbolAddress with that device current) and kept here.
-constexpr size_t kStaticRecords = ((size_t)40 << 20) / sizeof(unsigned long long); // 40 MiB
+constexpr size_t kStaticRecords = ((size_t)48 << 20) / sizeof(unsigned long long); // 48 MiB
 static __device__ __align__(256) unsigned long long scratch[kStaticRecords];
 constexpr int kMaxDevices = 64;
 unsigned long long *g_static_scratch[kMaxDevices] = {};
@@ -235,6 +235,7 @@ int heinsen_scan_static(const void *a, const void *b, const void *x0, void *out,
     bool bnd = false;
     int st = make_call(a, b, x0, out, B, D, n, layout, flags, stream, c, bnd);
     if (st != HEINSEN_OK) return st;
+    c.scratch_budget = kStaticRecords; // the launchers choose tiles whose carries fit, if there are such
     const hs::ScratchNeed need = bnd ? hs::bnd_scratch(c) : hs::bdn_scratch(c);
     if (need.records != 0 && hs::kRecordBase + need.records > kStaticRecords) return HEINSEN_ERR_SCRATCH_LIMIT;
     std::lock_guard<std::mutex> lock(g_mutex);

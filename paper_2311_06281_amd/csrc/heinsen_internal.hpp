@@ -18,6 +18,7 @@ struct ScanCall {
     bool linear;          // linear-domain comparison path (no logarithms anywhere)
     bool bf16;            // a, b stored as bfloat16
     bool x0_scalar;       // one x0 for all sequences
+    size_t scratch_budget; // 64-bit words of scratch the call may use, header included (0: no limit)
     hipStream_t stream;
 };
 

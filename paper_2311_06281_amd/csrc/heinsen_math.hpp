@@ -18,6 +18,8 @@
 
 namespace hs {
 
+typedef unsigned long long rec_t; // a tagged carry record, see the end of this file
+
 // Sign words: bit 31 is the sign (1 = negative); the other 31 bits are undefined and every consumer
 // either ignores them or masks them.  This lets the raw bits of an input float serve as its sign word.
 
@@ -105,6 +107,37 @@ __device__ __forceinline__ State seg_apply(const State &x, const Seg &g)
         return r;
     }
     slae<SIGNED>(x.lx + g.A, SIGNED ? (x.s ^ g.sA) : 0u, g.M, g.sM, r.lx, r.s);
+    return r;
+}
+
+// The state handed from tile to tile along a long sequence is kept in float64, so that a chain of
+// thousands of links does not accumulate float32 rounding of the state itself.
+struct State64 {
+    double lx;
+    uint32_t s;
+};
+
+// seg_apply with the state kept in float64: only the (small) correction log2(1 +- 2^-|t|) is formed in
+// float32.
+template <int DOM>
+__device__ __forceinline__ State64 seg_apply64(const State64 &x, const Seg &g)
+{
+    constexpr bool SIGNED = DOM == kSigned;
+    if (DOM == kLinear) return State64{x.lx * (double)g.A + (double)g.M, 0u};
+    const double p = x.lx + (double)g.A;
+    const double q = (double)g.M;
+    const uint32_t sp = SIGNED ? (x.s ^ g.sA) : 0u;
+    const double m = fmax(p, q);
+    float t = (float)(p - q);
+    t = (p == q) ? 0.0f : t;
+    float e = exp2_hw(-fabsf(t));
+    State64 r;
+    r.s = 0u;
+    if (SIGNED) {
+        e = u2f(f2u(e) ^ ((sp ^ g.sM) & kSignBit));
+        r.s = (t >= 0.0f) ? sp : g.sM;
+    }
+    r.lx = m + (double)log2_hw(1.0f + e);
     return r;
 }
 
@@ -344,7 +377,6 @@ __device__ __forceinline__ uint32_t readlane_u(uint32_t v, int lane)
 // carries that launch's epoch.  tag = epoch << 2 | two user bits (signs).  Nothing has to be ordered on
 // the publishing side, nothing has to be cleared between launches (older epochs never match), and a
 // consumer gets flag and payload in one round trip.
-typedef unsigned long long rec_t;
 
 __device__ __forceinline__ void rec_put(rec_t *p, uint32_t payload, uint32_t epoch, uint32_t bits)
 {
@@ -358,6 +390,22 @@ __device__ __forceinline__ rec_t rec_get(const rec_t *p)
 __device__ __forceinline__ bool rec_ok(rec_t r, uint32_t epoch) { return ((uint32_t)(r >> 34)) == (epoch & 0x3fffffffu); }
 __device__ __forceinline__ uint32_t rec_payload(rec_t r) { return (uint32_t)r; }
 __device__ __forceinline__ uint32_t rec_bits(rec_t r) { return (uint32_t)(r >> 32) & 3u; }
+
+// A float64 state travels as two records: the high and low word of the double; the sign rides in the user
+// bits of the first.
+__device__ __forceinline__ void state64_put(rec_t *p_hi, rec_t *p_lo, const State64 &x, uint32_t epoch, bool with_sign)
+{
+    const unsigned long long bits = (unsigned long long)__double_as_longlong(x.lx);
+    rec_put(p_hi, (uint32_t)(bits >> 32), epoch, with_sign ? (x.s >> 31) : 0u);
+    rec_put(p_lo, (uint32_t)bits, epoch, 0u);
+}
+__device__ __forceinline__ State64 state64_from(rec_t r_hi, rec_t r_lo, bool with_sign)
+{
+    State64 x;
+    x.lx = __longlong_as_double((long long)(((unsigned long long)rec_payload(r_hi) << 32) | rec_payload(r_lo)));
+    x.s = with_sign ? (rec_bits(r_hi) << 31) : 0u;
+    return x;
+}
 
 // A segment summary is two records: {A, tag | sA, sM} and {M, tag}.
 template <int DOM>

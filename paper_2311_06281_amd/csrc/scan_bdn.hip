@@ -493,35 +493,6 @@ struct TileParams {
     Timeline tl;
 };
 
-struct State64 {
-    double lx;
-    uint32_t s;
-};
-
-// seg_apply with the state kept in float64: only the (small) correction log2(1 +- 2^-|t|) is formed in
-// float32, so a long chain does not accumulate float32 rounding of the state itself.
-template <int DOM>
-__device__ __forceinline__ State64 seg_apply64(const State64 &x, const Seg &g)
-{
-    constexpr bool SIGNED = DOM == kSigned;
-    if (DOM == kLinear) return State64{x.lx * (double)g.A + (double)g.M, 0u};
-    const double p = x.lx + (double)g.A;
-    const double q = (double)g.M;
-    const uint32_t sp = SIGNED ? (x.s ^ g.sA) : 0u;
-    const double m = fmax(p, q);
-    float t = (float)(p - q);
-    t = (p == q) ? 0.0f : t;
-    float e = exp2_hw(-fabsf(t));
-    State64 r;
-    r.s = 0u;
-    if (SIGNED) {
-        e = u2f(f2u(e) ^ ((sp ^ g.sM) & kSignBit));
-        r.s = (t >= 0.0f) ? sp : g.sM;
-    }
-    r.lx = m + (double)log2_hw(1.0f + e);
-    return r;
-}
-
 template <int DOM, bool LOG_IN, bool LOG_OUT, typename InT, bool VECIO, bool MULTI, int ITEMS>
 __device__ __forceinline__ void tiles_tile(const TileParams &p, const uint32_t tile, const uint32_t epoch)
 {

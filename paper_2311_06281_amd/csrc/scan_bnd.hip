@@ -48,8 +48,9 @@ struct BndParams {
     uint32_t draws_per_q; // workgroups per queue = grid size / nq
     rec_t *header;    // scratch header (ticket queues); null when the launch needs no carries
     rec_t *agg;       // [ntiles][2][CH]  tile summaries: plane 0 = {A | signs}, plane 1 = {M}
-    rec_t *state;     // [ngroups][ncols][CH] state at the start of a group: {log2|x| | sign}
-                      // (SG > 0: [nsuper][ncols][CH], at the start of a super-group of SG groups)
+    rec_t *state;     // [ngroups][ncols][2][CH] state at the start of a group: float64 log2|x| in two records
+                      // (high word | sign, low word)
+                      // (SG > 0: [nsuper][ncols][2][CH], at the start of a super-group of SG groups)
     rec_t *gagg;      // SG > 0: [ngroups][ncols][2][CH] group summaries, planes as in agg
     uint32_t spin_limit;
     uint32_t drop_tile;
@@ -136,7 +137,7 @@ __device__ __forceinline__ void bnd_tile(const BndParams &p, const uint32_t tile
     __shared__ float lds_A[TS][CH];
     __shared__ float lds_M[TS][CH];
     __shared__ uint32_t lds_S[SIGNED ? TS : 1][CH];
-    __shared__ float lds_startL[CH];
+    __shared__ double lds_startL[CH]; // float64: the wave that closes a group hands it on as it is
     __shared__ uint32_t lds_startS[CH];
 
     const int lane = threadIdx.x & 63;
@@ -184,11 +185,15 @@ __device__ __forceinline__ void bnd_tile(const BndParams &p, const uint32_t tile
     //      flight: once the kernel is past its first round the earlier tiles of the group have usually
     //      published, and the records then arrive ahead of the tile's own loads at no cost in latency ---
     const bool first = ts == 0; // wave-uniform
-    rec_t rA[GP], rM[GP], rS = 0;
+    rec_t rA[GP], rM[GP], rS = 0, rS2 = 0;
     const int q = SG > 0 ? g / (SG > 0 ? SG : 1) : 0;  // super-group, and the group's place in it
     const int gi = SG > 0 ? g % (SG > 0 ? SG : 1) : 0;
     auto issue_records = [&]() {
-        if (SG == 0 && g > 0) rS = rec_get(p.state + ((size_t)g * p.ncols + col) * CH + c);
+        if (SG == 0 && g > 0) {
+            const rec_t *sp = p.state + ((size_t)g * p.ncols + col) * (2 * CH) + c;
+            rS = rec_get(sp);
+            rS2 = rec_get(sp + CH);
+        }
 #pragma unroll
         for (int j = 0; j < G - 1; ++j) {
             if (j < r) {
@@ -200,7 +205,7 @@ __device__ __forceinline__ void bnd_tile(const BndParams &p, const uint32_t tile
     };
     auto records_in = [&]() -> bool { // this lane's records carry the launch's tag
         bool ok = true;
-        if (SG == 0 && g > 0) ok = rec_ok(rS, epoch);
+        if (SG == 0 && g > 0) ok = rec_ok(rS, epoch) && rec_ok(rS2, epoch);
 #pragma unroll
         for (int j = 0; j < G - 1; ++j) {
             if (j < r) ok = ok && rec_ok(rA[j], epoch) && rec_ok(rM[j], epoch);
@@ -267,7 +272,14 @@ __device__ __forceinline__ void bnd_tile(const BndParams &p, const uint32_t tile
     }
     p.tl.mark(tile, 3);
 
-    State st; // state at the wave's first step
+    State st;                // state at the wave's first step
+    State64 st64{0.0, 0u};   // the same in float64, along the chain of tiles
+    auto state_from_x0 = [&]() {
+        float x0v = LOG_IN ? 0.0f : 1.0f, lx;
+        if (chan_ok) x0v = p.x0[p.x0_stride ? x0_at : 0];
+        encode<DOM, LOG_IN>(x0v, lx, st64.s);
+        st64.lx = (double)lx;
+    };
     if (first) {
         // ---- obtain the state at the start of the tile ------------------------------------------
         if (!have_records) issue_records();
@@ -296,7 +308,11 @@ __device__ __forceinline__ void bnd_tile(const BndParams &p, const uint32_t tile
             if (lost) grp.M = __builtin_nanf("");
             // second round: the state at the start of the super-group and the earlier groups of it
             auto issue2 = [&]() {
-                if (q > 0) rS = rec_get(p.state + ((size_t)q * p.ncols + col) * CH + c);
+                if (q > 0) {
+                    const rec_t *sp = p.state + ((size_t)q * p.ncols + col) * (2 * CH) + c;
+                    rS = rec_get(sp);
+                    rS2 = rec_get(sp + CH);
+                }
 #pragma unroll
                 for (int j = 0; j < SG - 1; ++j) {
                     if (j < gi) {
@@ -308,7 +324,7 @@ __device__ __forceinline__ void bnd_tile(const BndParams &p, const uint32_t tile
             };
             auto in2 = [&]() -> bool {
                 bool ok = true;
-                if (q > 0) ok = rec_ok(rS, epoch);
+                if (q > 0) ok = rec_ok(rS, epoch) && rec_ok(rS2, epoch);
 #pragma unroll
                 for (int j = 0; j < SG - 1; ++j) {
                     if (j < gi) ok = ok && rec_ok(rA[j], epoch) && rec_ok(rM[j], epoch);
@@ -330,25 +346,24 @@ __device__ __forceinline__ void bnd_tile(const BndParams &p, const uint32_t tile
                 }
             }
             if (q == 0) {
-                float x0v = LOG_IN ? 0.0f : 1.0f;
-                if (chan_ok) x0v = p.x0[p.x0_stride ? x0_at : 0];
-                encode<DOM, LOG_IN>(x0v, st.lx, st.s);
+                state_from_x0();
             } else {
-                st.lx = u2f(rec_payload(rS));
-                st.s = SIGNED ? (rec_bits(rS) << 31) : 0u;
+                st64 = state64_from(rS, rS2, SIGNED);
             }
 #pragma unroll
             for (int j = 0; j < SG - 1; ++j) {
-                if (j < gi) st = seg_apply<DOM>(st, seg_from<DOM>(rA[j], rM[j]));
+                if (j < gi) st64 = seg_apply64<DOM>(st64, seg_from<DOM>(rA[j], rM[j]));
             }
-            st = seg_apply<DOM>(st, grp);
+            st64 = seg_apply64<DOM>(st64, grp);
             if (lost) {
-                st.lx = __builtin_nanf("");
+                st64.lx = __builtin_nan("");
                 note_wait_gave_up(p.header);
             }
+            st.lx = (float)st64.lx;
+            st.s = st64.s;
             if (TS > 1) {
-                lds_startL[c] = st.lx;
-                lds_startS[c] = st.s;
+                lds_startL[c] = st64.lx;
+                lds_startS[c] = st64.s;
                 // the wave that closes the tile also needs the fold of the earlier tiles of the group (the
                 // last slot of the summaries is free: the closing wave never writes its own there)
                 lds_A[TS - 1][c] = grp.A;
@@ -366,31 +381,30 @@ __device__ __forceinline__ void bnd_tile(const BndParams &p, const uint32_t tile
                     seg_put<DOM>(gp, gp + CH, seg_combine<DOM>(grp, run), epoch);
                 }
                 if (more && r == G - 1 && gi == SG - 1) {
-                    const State nx = seg_apply<DOM>(st, run);
-                    rec_put(p.state + ((size_t)(q + 1) * p.ncols + col) * CH + c, f2u(nx.lx), epoch, SIGNED ? (nx.s >> 31) : 0u);
+                    rec_t *sp = p.state + ((size_t)(q + 1) * p.ncols + col) * (2 * CH) + c;
+                    state64_put(sp, sp + CH, seg_apply64<DOM>(st64, run), epoch, SIGNED);
                 }
             }
         } else {
             if (g == 0) {
-                float x0v = LOG_IN ? 0.0f : 1.0f;
-                if (chan_ok) x0v = p.x0[p.x0_stride ? x0_at : 0];
-                encode<DOM, LOG_IN>(x0v, st.lx, st.s);
+                state_from_x0();
             } else {
-                st.lx = u2f(rec_payload(rS));
-                st.s = SIGNED ? (rec_bits(rS) << 31) : 0u;
+                st64 = state64_from(rS, rS2, SIGNED);
             }
             // fold the earlier tiles of the group in tile order
 #pragma unroll
             for (int j = 0; j < G - 1; ++j) {
-                if (j < r) st = seg_apply<DOM>(st, seg_from<DOM>(rA[j], rM[j]));
+                if (j < r) st64 = seg_apply64<DOM>(st64, seg_from<DOM>(rA[j], rM[j]));
             }
             if (lost) {
-                st.lx = __builtin_nanf("");
+                st64.lx = __builtin_nan("");
                 note_wait_gave_up(p.header);
             }
+            st.lx = (float)st64.lx;
+            st.s = st64.s;
             if (TS > 1) {
-                lds_startL[c] = st.lx;
-                lds_startS[c] = st.s;
+                lds_startL[c] = st64.lx;
+                lds_startS[c] = st64.s;
                 lds_signal(&flag_start[wc]);
             } else {
                 // a single wave along time closes the tile itself
@@ -399,8 +413,8 @@ __device__ __forceinline__ void bnd_tile(const BndParams &p, const uint32_t tile
                     seg_put<DOM>(tp, tp + CH, run, epoch);
                 }
                 if (more && r == G - 1) {
-                    const State nx = seg_apply<DOM>(st, run);
-                    rec_put(p.state + ((size_t)(g + 1) * p.ncols + col) * CH + c, f2u(nx.lx), epoch, SIGNED ? (nx.s >> 31) : 0u);
+                    rec_t *sp = p.state + ((size_t)(g + 1) * p.ncols + col) * (2 * CH) + c;
+                    state64_put(sp, sp + CH, seg_apply64<DOM>(st64, run), epoch, SIGNED);
                 }
             }
         }
@@ -430,8 +444,10 @@ __device__ __forceinline__ void bnd_tile(const BndParams &p, const uint32_t tile
             }
         }
         lds_await(&flag_start[wc]);
-        st.lx = lds_startL[c];
-        st.s = lds_startS[c];
+        st64.lx = lds_startL[c];
+        st64.s = lds_startS[c];
+        st.lx = (float)st64.lx;
+        st.s = st64.s;
         if (closing && more && r == G - 1) {
             if constexpr (SG > 0) {
                 Seg grp;
@@ -443,13 +459,13 @@ __device__ __forceinline__ void bnd_tile(const BndParams &p, const uint32_t tile
                     rec_t *gp = p.gagg + ((size_t)g * p.ncols + col) * (2 * CH) + c;
                     seg_put<DOM>(gp, gp + CH, seg_combine<DOM>(grp, total), epoch);
                 } else {
-                    const State nx = seg_apply<DOM>(st, total);
-                    rec_put(p.state + ((size_t)(q + 1) * p.ncols + col) * CH + c, f2u(nx.lx), epoch, SIGNED ? (nx.s >> 31) : 0u);
+                    rec_t *sp = p.state + ((size_t)(q + 1) * p.ncols + col) * (2 * CH) + c;
+                    state64_put(sp, sp + CH, seg_apply64<DOM>(st64, total), epoch, SIGNED);
                 }
             } else {
                 // last tile of a group: the state after this tile starts the next group
-                const State nx = seg_apply<DOM>(st, total);
-                rec_put(p.state + ((size_t)(g + 1) * p.ncols + col) * CH + c, f2u(nx.lx), epoch, SIGNED ? (nx.s >> 31) : 0u);
+                rec_t *sp = p.state + ((size_t)(g + 1) * p.ncols + col) * (2 * CH) + c;
+                state64_put(sp, sp + CH, seg_apply64<DOM>(st64, total), epoch, SIGNED);
             }
         }
         st = seg_apply<DOM>(st, pre);
@@ -566,7 +582,7 @@ struct BndPlan {
     size_t off_agg, off_gagg, off_state, records; // in records, relative to kRecordBase
 };
 
-BndPlan make_plan(const ScanCall &c)
+BndPlan make_plan(const ScanCall &c, bool allow_wide = true)
 {
     BndPlan pl;
     // Default tile: 64 channels x 256 steps (8 waves one after the other along time, 32 steps each;
@@ -586,7 +602,7 @@ BndPlan make_plan(const ScanCall &c)
     } else if (c.n <= 128) {
         // short sequences: no more waves than have steps to work on
         pl.NW = c.n <= 32 ? 1 : (c.n <= 64 ? 2 : 4);
-    } else if (c.D % 128 == 0 && c.B * (c.D / 128) >= 2 * kMinColsPerQueueWide && c.n >= 1024) {
+    } else if (allow_wide && c.D % 128 == 0 && c.B * (c.D / 128) >= 2 * kMinColsPerQueueWide && c.n >= 1024) {
         pl.cg = 2;
     }
     pl.CH = 64 * pl.cg;
@@ -629,7 +645,7 @@ BndPlan make_plan(const ScanCall &c)
     pl.off_agg = 0;
     pl.off_gagg = (size_t)pl.ntiles * 2 * pl.CH;
     pl.off_state = pl.off_gagg + (pl.SG ? (size_t)pl.ngroups * pl.ncols * 2 * pl.CH : 0);
-    pl.records = pl.off_state + (size_t)(pl.SG ? ceil_div(pl.ngroups, pl.SG) + 1 : pl.ngroups) * pl.ncols * pl.CH;
+    pl.records = pl.off_state + (size_t)(pl.SG ? ceil_div(pl.ngroups, pl.SG) + 1 : pl.ngroups) * pl.ncols * 2 * pl.CH;
     pl.ticketless = pl.nchunks == 1 && c.n <= 64; // short single-tile columns: no records, no tickets
     // A queue's workgroups that find no tile behind their ticket (uneven deal) end at once.
     pl.nq = kQueues;
@@ -641,6 +657,8 @@ BndPlan make_plan(const ScanCall &c)
     } else {
         pl.grid = (uint32_t)pl.nq * (uint32_t)pl.cols_per_q * (uint32_t)pl.nchunks;
     }
+    // the wide tiles take twice the records: a caller with a fixed scratch buffer may have to do without them
+    if (pl.cg > 1 && c.scratch_budget != 0 && kRecordBase + pl.records > c.scratch_budget) return make_plan(c, false);
     return pl;
 }
 

@@ -155,3 +155,31 @@ def test_long_sequences_of_few_columns(gpu, D, n):
     nbad, worst = violations(cfg, got, ref)
     print(f"[full] worst error/bound {worst:.3g}", flush=True)
     assert nbad == 0, f"{nbad} of {ref.size} outside the tolerance (worst {worst:.3g})"
+
+
+@pytest.mark.parametrize("B,D,n", [(1, 64, 1 << 22), (1, 64, 1 << 23), (4, 64, 1 << 20), (2, 8, 1 << 21), (2, 1024, 1 << 17)])
+def test_long_slowly_decaying_sequences_channel_contiguous(gpu, B, D, n):
+    """[B,n,D] with coefficients within 1e-4 of 1 (configuration 3's distribution) over millions of steps,
+    held to the positive tolerance of the definition (1e-4 relative): the state that travels from one group
+    of tiles to the next goes through n/1024 .. n/16384 links (one column: two carry levels of 8 x 8 tiles;
+    four columns: 4 x 4; narrow channels packed side by side; 32 columns: plain groups of eight) and has to
+    be carried in float64 to stay inside the bound.  Generated and checked in full against the float64
+    sequential oracle."""
+    torch, hb = gpu
+    import bench
+
+    cfg = workloads.Config(3, B, D, n, "BND", ("POSITIVE",), False, name="slowly decaying, channel-contiguous")
+    print(f"[full] cfg3 distribution in [B,n,D] {cfg.shape()}", flush=True)
+    a, b, x0, out = bench.device_inputs(cfg, torch, distinct=B)
+    hb.heinsen_scan(a, b, x0, out, cfg.B, cfg.D, cfg.n, hb.LAYOUTS[cfg.layout], hb.flags_from_names(cfg.flags),
+                    torch.cuda.current_stream())
+    torch.cuda.synchronize()
+    got = out.cpu().numpy()
+    del a, b, x0, out
+    torch.cuda.empty_cache()
+    ref = reference(cfg, workloads.generate(cfg), threads=16)
+    rel = np.abs(got - ref) / np.abs(ref)
+    print(f"[full] max relative error {rel.max():.3g} (bound 1e-4)", flush=True)
+    nbad, worst = violations(cfg, got, ref)
+    print(f"[full] worst error/bound {worst:.3g}", flush=True)
+    assert nbad == 0, f"{nbad} of {ref.size} outside the tolerance (worst {worst:.3g})"

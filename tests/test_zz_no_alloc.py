@@ -57,6 +57,33 @@ def test_static_entry_point_matches_the_allocating_one(gpu, first, second):
         assert np.array_equal(got.view(np.uint32), want.view(np.uint32))
 
 
+def test_static_entry_point_with_narrower_tiles_than_the_allocating_one(gpu):
+    """[16, 12288, 2048]: heinsen_scan takes its wide tiles (carries: 63 MiB), the fixed 48 MiB array only
+    holds the narrower ones (31 MiB).  Both are the same method with different float32 rounding: the
+    result is held to the signed tolerance with the allocating entry point's output as the reference."""
+    torch, hb = gpu
+    from parity import violations
+
+    cfg = workloads.CONFIGS[5].scaled(n=12288)
+    batch = workloads.generate(cfg, 0, 1)
+    rep = lambda x: torch.from_numpy(x).to("cuda:0").repeat((cfg.B,) + (1,) * (x.ndim - 1)).contiguous()
+    a, b = rep(batch.a), rep(batch.b)
+    x0 = torch.from_numpy(batch.x0).to("cuda:0").repeat(cfg.B).contiguous()
+    layout, flags = hb.LAYOUTS[cfg.layout], hb.flags_from_names(cfg.flags)
+    stream = torch.cuda.current_stream()
+    want = torch.empty_like(a)
+    got = torch.empty_like(a)
+    print(f"[no-alloc] cfg5 distribution B={cfg.B}: wide tiles against narrow tiles", flush=True)
+    hb.heinsen_scan(a, b, x0, want, cfg.B, cfg.D, cfg.n, layout, flags, stream)
+    hb.heinsen_scan_static(a, b, x0, got, cfg.B, cfg.D, cfg.n, layout, flags, stream)
+    torch.cuda.synchronize()
+    one = cfg.scaled(B=1)
+    for bi in (0, cfg.B - 1):
+        nbad, worst = violations(one, got[bi:bi + 1].cpu().numpy(), want[bi:bi + 1].cpu().numpy().astype(np.float64))
+        print(f"[no-alloc] batch item {bi}: worst difference/bound {worst:.3g}", flush=True)
+        assert nbad == 0
+
+
 def test_static_entry_point_refuses_what_does_not_fit(gpu):
     torch, hb = gpu
     # [32, 32768, 2048] needs about 150 MiB of carry records; the pointers are never used
