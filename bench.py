@@ -288,6 +288,39 @@ def tile_timeline(cfg, torch, hb, launches=4):
     return "\n".join(lines)
 
 
+def flag_sweep(cfg, torch, hb, runs=30):
+    """The workload's shape, layout and storage type with other flag sets, i.e. the same bytes with less (or
+    other) arithmetic: tells whether the kernel is bound by memory or by its instructions.  Inputs are the
+    workload's own buffers, read as whatever the flags say (timing only).  Returns a text report."""
+    a, b, x0, out = device_inputs(cfg, torch)
+    stream = torch.cuda.current_stream()
+    layout = hb.LAYOUTS[cfg.layout]
+    store = hb.HEINSEN_IN_BF16 if cfg.bf16 else 0
+    sets = [("the workload's own flags", hb.flags_from_names(cfg.flags)),
+            ("LOG_INPUTS (logs in, x out: one log-add-exp less per element)", hb.HEINSEN_LOG_INPUTS | store),
+            ("POSITIVE (x in, x out)", hb.HEINSEN_POSITIVE | store),
+            ("signed (x in, x out, signs tracked)", store),
+            ("LINEAR (no logarithm or exponential at all)", hb.HEINSEN_LINEAR | store)]
+    lines = [f"workload cfg{cfg.index} {cfg.shape()} {cfg.layout}, {cfg.bytes_per_element} B/element, mean of {runs} launches after 40 untimed ones"]
+    for name, flags in sets:
+        fn = lambda: hb.heinsen_scan(a, b, x0, out, cfg.B, cfg.D, cfg.n, layout, flags, stream)
+        for _ in range(40):
+            fn()
+        first, last = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        first.record(stream)
+        for _ in range(runs):
+            fn()
+        last.record(stream)
+        torch.cuda.synchronize()
+        ms = first.elapsed_time(last) / runs
+        gbs = cfg.bytes_per_element * cfg.elements / (ms * 1e-3) / 1e9
+        lines.append(f"  {name:64s} {ms * 1e3:8.1f} us  {gbs:6.0f} GB/s  {gbs / HBM_PEAK_GBS:.3f} of peak  "
+                     f"({hb.heinsen_kernel_name(cfg.B, cfg.D, cfg.n, layout, flags)})")
+    del a, b, x0, out
+    torch.cuda.empty_cache()
+    return "\n".join(lines)
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -300,6 +333,8 @@ def main() -> int:
                     help="instead of the benchmark, run the paper's sequential-vs-parallel sweep over n (Fig. 1)")
     ap.add_argument("--timeline", type=int, default=0, metavar="CFG",
                     help="instead of the benchmark, print the per-tile timeline of one launch of configuration CFG (2, 3 or 5)")
+    ap.add_argument("--flag-sweep", type=int, default=0, metavar="CFG",
+                    help="instead of the benchmark, time configuration CFG's shape with flag sets of less arithmetic")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run plain device copies of a known size (reference for rocprofv3 FETCH_SIZE/WRITE_SIZE)")
     args = ap.parse_args()
@@ -325,6 +360,10 @@ def main() -> int:
 
     if args.timeline:
         print(tile_timeline(workloads.CONFIGS[args.timeline], torch, hb))
+        return 0
+
+    if args.flag_sweep:
+        print(flag_sweep(workloads.CONFIGS[args.flag_sweep], torch, hb))
         return 0
 
     if args.copy_calibration:

@@ -22,7 +22,12 @@ import numpy as np
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_HERE, "heinsen_oracle.c")
-_LIB = os.path.join(_HERE, "libheinsen_oracle.so")
+# HEINSEN_ORACLE_SANITIZE=1: a second build with AddressSanitizer and UndefinedBehaviorSanitizer (CPU only), to
+# be run with libasan preloaded, e.g.
+#   LD_PRELOAD="$(gcc -print-file-name=libasan.so) $LD_PRELOAD" ASAN_OPTIONS=detect_leaks=0 \
+#   HEINSEN_ORACLE_SANITIZE=1 python -m pytest tests/test_oracle_pins.py -q
+_SANITIZE = os.environ.get("HEINSEN_ORACLE_SANITIZE", "") == "1"
+_LIB = os.path.join(_HERE, "libheinsen_oracle_san.so" if _SANITIZE else "libheinsen_oracle.so")
 
 LAYOUT_BND = 0  # [B, n, D]
 LAYOUT_BDN = 1  # [B, D, n]
@@ -33,8 +38,9 @@ _lib = None
 def build(force: bool = False) -> str:
     """Compile the C oracle with gcc (no fast-math, no FMA contraction). Returns the .so path."""
     if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        extra = ["-g", "-fsanitize=address,undefined", "-fno-sanitize-recover=undefined"] if _SANITIZE else []
         cmd = ["gcc", "-O2", "-ffp-contract=off", "-fno-fast-math", "-fopenmp", "-shared", "-fPIC",
-               "-std=gnu11", "-o", _LIB, _SRC, "-lm"]
+               "-std=gnu11", *extra, "-o", _LIB, _SRC, "-lm"]
         subprocess.run(cmd, check=True)
     return _LIB
 

@@ -35,13 +35,13 @@ struct ScanCall {
 // 1 .. 2^30 - 1; the launch that has the last one clears the records when its last workgroup ends.
 // Other header words: the buffer's size, an error word (a carry wait that gave up), and the two counters
 // just named.  Records start at kRecordBase.
-constexpr size_t kRecordBase = 256;
 constexpr int kQueues = 8;                 // one per compute die
 constexpr size_t kQueueStride = 16;        // words between queue counters (128 bytes)
-constexpr size_t kHeaderCapacity = 128;    // size of the buffer in words, header included
-constexpr size_t kHeaderError = 129;       // non-zero: some tile gave up waiting for a carry record
-constexpr size_t kHeaderQueuesDone = 144;  // queues of the current launch that have handed out all their tickets
-constexpr size_t kHeaderExited = 160;      // workgroups that have ended (counted only by the launch that clears)
+constexpr size_t kHeaderCapacity = kQueueStride * kQueues;    // size of the buffer in words, header included
+constexpr size_t kHeaderError = kHeaderCapacity + 1;          // non-zero: some tile gave up waiting for a carry record
+constexpr size_t kHeaderQueuesDone = kHeaderCapacity + 16;    // queues of the current launch that have handed out all their tickets
+constexpr size_t kHeaderExited = kHeaderCapacity + 32;        // workgroups that have ended (counted only by the launch that clears)
+constexpr size_t kRecordBase = kHeaderCapacity + 128;
 constexpr uint32_t kLastEpoch = (1u << 30) - 1u;
 
 // What the host tells a launch that uses carry records.

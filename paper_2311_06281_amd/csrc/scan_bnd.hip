@@ -602,6 +602,7 @@ BndPlan make_plan(const ScanCall &c, bool allow_wide = true)
     } else if (c.n <= 128) {
         // short sequences: no more waves than have steps to work on
         pl.NW = c.n <= 32 ? 1 : (c.n <= 64 ? 2 : 4);
+
     } else if (allow_wide && c.D % 128 == 0 && c.B * (c.D / 128) >= 2 * kMinColsPerQueueWide && c.n >= 1024) {
         pl.cg = 2;
     }

@@ -390,3 +390,45 @@ def test_bf16_rounding_is_nearest_even_and_widening_exact():
     # 1 + 2^-8 is a tie between 1.0 and 1 + 2^-7 -> even (1.0); 1 + 3*2^-8 ties to 1 + 2^-6
     assert back[0] == 1.0 and back[1] == 1.0 and back[2] == np.float32(1.015625) and back[3] == -3.0
     assert np.all(np.abs(back - x) <= np.abs(x) * 2.0 ** -8)
+
+
+def test_log_domain_definition_with_zero_and_infinite_terms():
+    """The log-domain form of the definition (Sec. 3, logarithms taken term by term) where a term is
+    exactly zero (logarithm -inf: x_0 = 0, b_t = 0, a_t = 0) or infinite: equal to the logarithm of the
+    linear definition evaluated on the exponentiated inputs, -inf and +inf included."""
+    ninf = -np.inf
+    la = np.log(np.array([0.5, 2.0, 0.25, 1.0, 3.0, 0.5, 2.0], dtype=np.float64))
+    lb = np.array([ninf, ninf, np.log(1.5), ninf, np.log(0.125), ninf, np.log(2.0)])
+    la[5] = ninf  # a_6 = 0: the sequence restarts at b_6 = 0, then at b_7
+    for lx0 in (ninf, 0.0):
+        a32, b32 = la.astype(np.float32).reshape(1, 1, -1), lb.astype(np.float32).reshape(1, 1, -1)
+        got = oracle.sequential_log(a32, b32, np.array([lx0], dtype=np.float32))
+        with np.errstate(divide="ignore"):
+            want = np.log(oracle.sequential(np.exp(a32.astype(np.float64)).astype(np.float32),
+                                            np.exp(b32.astype(np.float64)).astype(np.float32),
+                                            np.exp(np.array([lx0])).astype(np.float32)))
+        assert np.array_equal(np.isneginf(got), np.isneginf(want))
+        fin = np.isfinite(want)
+        assert fin.sum() >= 3 and np.allclose(got[fin], want[fin], rtol=1e-6, atol=1e-6)
+    if True:  # an infinite term swallows everything after it
+        lb2 = lb.copy()
+        lb2[2] = np.inf
+        got = oracle.sequential_log(la.astype(np.float32).reshape(1, 1, -1), lb2.astype(np.float32).reshape(1, 1, -1),
+                                    np.array([0.0], dtype=np.float32)).reshape(-1)
+        assert np.isfinite(got[:2]).all() and np.isposinf(got[2:5]).all()
+        assert np.isneginf(got[5]) and got[6] == pytest.approx(np.log(2.0))  # a_6 = 0 forgets even that
+
+
+def test_scaled_complex_log_below_the_float64_range_of_exp():
+    """seq_clog_scaled carries x as sign * exp(l); when l < -700 (|x| below 1e-304) it multiplies by exp(l)
+    instead of dividing by it.  A state that small still has a plain float64 value, so the plain complex
+    logarithm of the definition pins that branch; so does the closed form for b = 0."""
+    x0 = 1e-320  # subnormal: log = -737
+    a = np.array([2.0, -3.0, 0.5, 1e10])
+    for b in (np.zeros(4), np.array([0.0, 0.0, 1e-315, 0.0]), np.array([3.0, 0.0, -1.0, 2.0])):
+        got = oracle.seq_clog_scaled(a, b, x0)
+        x = x0
+        for t in range(4):
+            x = a[t] * x + b[t]
+            assert got[t].real == pytest.approx(np.log(abs(x)), rel=1e-3 if abs(x) < 1e-300 else 1e-12)
+            assert got[t].imag == (np.pi if x < 0 else 0.0)
