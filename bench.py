@@ -288,6 +288,45 @@ def tile_timeline(cfg, torch, hb, launches=4):
     return "\n".join(lines)
 
 
+def stream_probe(cfg, torch, hb, runs=20):
+    """Ceilings of the access patterns (heinsen_stream_probe: out = a + b, nothing else) on buffers of
+    configuration `cfg`'s size, beside torch's own add and copy.  Returns a text report."""
+    B, n, D = cfg.B, cfg.n, cfg.D
+    E = B * n * D
+    a = torch.rand(E, dtype=torch.float32, device="cuda")
+    b = torch.rand(E, dtype=torch.float32, device="cuda")
+    out = torch.empty_like(a)
+    stream = torch.cuda.current_stream()
+
+    def timed(fn, nbytes):
+        for _ in range(40):
+            fn()
+        first, last = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        first.record(stream)
+        for _ in range(runs):
+            fn()
+        last.record(stream)
+        torch.cuda.synchronize()
+        ms = first.elapsed_time(last) / runs
+        return ms * 1e3, nbytes / (ms * 1e-3) / 1e9
+
+    names = ["one long vector, 16 B per lane", "tiles 64 ch x 256 steps (rows of 256 B)", "tiles 128 ch x 128 steps (rows of 512 B)",
+             "tiles 256 ch x 64 steps (rows of 1 KiB)", "64 x 256, stores after all loads", "128 x 128, stores after all loads",
+             "256 x 64, stores after all loads"]
+    lines = [f"out = a + b on [B={B}, n={n}, D={D}] float32 ({12 * E / 1e6:.0f} MB per launch), mean of {runs} launches after 40 untimed ones"]
+    for pat, nm in enumerate(names):
+        if hb.heinsen_stream_probe_status(a, b, out, B, n, D, pat, stream) != hb.HEINSEN_OK:
+            lines.append(f"  heinsen_stream_probe {pat}: {nm:44s} not applicable to this shape")
+            continue
+        us, gbs = timed(lambda: hb.heinsen_stream_probe_status(a, b, out, B, n, D, pat, stream), 12 * E)
+        lines.append(f"  heinsen_stream_probe {pat}: {nm:44s} {us:8.1f} us  {gbs:6.0f} GB/s  {gbs / HBM_PEAK_GBS:.3f} of peak")
+    us, gbs = timed(lambda: torch.add(a, b, out=out), 12 * E)
+    lines.append(f"  torch.add(a, b, out=o)  {'':47s} {us:8.1f} us  {gbs:6.0f} GB/s  {gbs / HBM_PEAK_GBS:.3f} of peak")
+    us, gbs = timed(lambda: out.copy_(a), 8 * E)
+    lines.append(f"  o.copy_(a)              {'':47s} {us:8.1f} us  {gbs:6.0f} GB/s  {gbs / HBM_PEAK_GBS:.3f} of peak")
+    return "\n".join(lines)
+
+
 def flag_sweep(cfg, torch, hb, runs=30):
     """The workload's shape, layout and storage type with other flag sets, i.e. the same bytes with less (or
     other) arithmetic: tells whether the kernel is bound by memory or by its instructions.  Inputs are the
@@ -333,6 +372,8 @@ def main() -> int:
                     help="instead of the benchmark, run the paper's sequential-vs-parallel sweep over n (Fig. 1)")
     ap.add_argument("--timeline", type=int, default=0, metavar="CFG",
                     help="instead of the benchmark, print the per-tile timeline of one launch of configuration CFG (2, 3 or 5)")
+    ap.add_argument("--stream-probe", type=int, default=0, metavar="CFG",
+                    help="instead of the benchmark, measure the streaming ceilings of the access patterns on CFG's size")
     ap.add_argument("--flag-sweep", type=int, default=0, metavar="CFG",
                     help="instead of the benchmark, time configuration CFG's shape with flag sets of less arithmetic")
     ap.add_argument("--copy-calibration", action="store_true",
@@ -360,6 +401,10 @@ def main() -> int:
 
     if args.timeline:
         print(tile_timeline(workloads.CONFIGS[args.timeline], torch, hb))
+        return 0
+
+    if args.stream_probe:
+        print(stream_probe(workloads.CONFIGS[args.stream_probe], torch, hb))
         return 0
 
     if args.flag_sweep:

@@ -187,6 +187,20 @@ int heinsen_kernel_name(int64_t B, int64_t D, int64_t n, int layout, uint32_t fl
 int heinsen_sequential(const void *a, const void *b, const void *x0, void *out, int64_t n, void *stream);
 
 /*
+ * heinsen_stream_probe -- measurement aid: out = a + b over a [B, n, D] float32 array (device pointers,
+ * B*n*D elements each) with nothing but the memory access pattern of a scan kernel, all accesses
+ * non-temporal.  What it reaches is the ceiling of that pattern on the machine at hand, the yardstick
+ * beside the published peak.  pattern: 0 the array as one long vector, 16 bytes per lane; 1 the default
+ * tile of the [B, n, D] kernel (workgroup = 64 channels x 256 steps, rows of 256 bytes); 2 its wide tile
+ * (128 channels x 128 steps, rows of 512 bytes); 3 256 channels x 64 steps; 4, 5, 6 = 1, 2, 3 with no output
+ * stored before all of a lane's inputs have arrived, as in a scan.  Patterns 1..6 need D a multiple of
+ * 64, 128, 256 and n a multiple of 256, 128, 64 (HEINSEN_ERR_UNSUPPORTED otherwise).  Asynchronous on
+ * `stream`.  Returns a heinsen_status_t.
+ */
+int heinsen_stream_probe(const void *a, const void *b, void *out, int64_t B, int64_t n, int64_t D, int pattern,
+                         void *stream);
+
+/*
  * heinsen_set_timeline -- profiling aid (the per-tile view that a kernel-level profiler cannot give).
  * While set, every tile of every later launch of the two carry-chained kernels writes eight 64-bit
  * time stamps of the GPU's 100 MHz wall clock to stamps[tile * 8 + i], for tiles below `tiles`:

@@ -37,7 +37,7 @@ HEINSEN_ERR_CARRY_LOST = 6
 
 EXPORTS = ("heinsen_scan", "heinsen_scan_static", "heinsen_status_string", "heinsen_last_hip_error", "heinsen_version",
            "heinsen_release_scratch", "heinsen_kernel_name", "heinsen_sequential", "heinsen_check",
-           "heinsen_set_timeline", "heinsen_test_carry")
+           "heinsen_set_timeline", "heinsen_test_carry", "heinsen_stream_probe")
 
 _lib = None
 
@@ -76,6 +76,8 @@ def load() -> ctypes.CDLL:
         lib.heinsen_set_timeline.restype = ci
         lib.heinsen_test_carry.argtypes = [u32, u32, u32, vp]
         lib.heinsen_test_carry.restype = ci
+        lib.heinsen_stream_probe.argtypes = [vp, vp, vp, i64, i64, i64, ci, vp]
+        lib.heinsen_stream_probe.restype = ci
         lib.heinsen_sequential.argtypes = [vp, vp, vp, vp, i64, vp]
         lib.heinsen_sequential.restype = ci
         _lib = lib
@@ -181,6 +183,12 @@ def heinsen_test_carry(spin_limit: int = 0, drop_tile: int = 0xFFFFFFFF, epoch: 
     st = int(load().heinsen_test_carry(int(spin_limit), int(drop_tile), int(epoch), _stream_handle(stream)))
     if st != HEINSEN_OK:
         raise HeinsenError(st, heinsen_status_string(st))
+
+
+def heinsen_stream_probe_status(a, b, out, B: int, n: int, D: int, pattern: int, stream=None) -> int:
+    """out = a + b with the access pattern `pattern` of the scan kernels; see include/heinsen.h."""
+    return int(load().heinsen_stream_probe(_addr(a), _addr(b), _addr(out), int(B), int(n), int(D), int(pattern),
+                                           _stream_handle(stream)))
 
 
 def heinsen_sequential(a, b, x0, out, n: int, stream=None) -> None:

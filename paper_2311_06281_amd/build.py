@@ -9,7 +9,7 @@ from concurrent.futures import ThreadPoolExecutor
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libheinsen.so")
-SOURCES = ["heinsen_api.hip", "scan_bnd.hip", "scan_bdn.hip", "sequential_ref.hip"]
+SOURCES = ["heinsen_api.hip", "scan_bnd.hip", "scan_bdn.hip", "sequential_ref.hip", "stream_probe.hip"]
 HEADERS = ["heinsen_internal.hpp", "heinsen_math.hpp", "heinsen_tickets.hpp", os.path.join("..", "..", "include", "heinsen.h")]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-command-line-argument",

@@ -111,3 +111,17 @@ def test_per_tile_time_stamps(gpu):
     stamps.zero_()
     _run(cfg, dev, torch, hb)
     assert int(stamps.abs().sum().item()) == 0  # switched off again
+
+
+def test_stream_probe_adds(gpu):
+    """The yardstick kernels compute out = a + b for every pattern that applies to the shape."""
+    torch, hb = gpu
+    B, n, D = 2, 512, 512
+    a = torch.rand(B * n * D, dtype=torch.float32, device="cuda:0")
+    b = torch.rand(B * n * D, dtype=torch.float32, device="cuda:0")
+    for pattern in range(7):
+        out = torch.zeros_like(a)
+        assert hb.heinsen_stream_probe_status(a, b, out, B, n, D, pattern, torch.cuda.current_stream()) == hb.HEINSEN_OK
+        torch.cuda.synchronize()
+        assert torch.equal(out, a + b), f"pattern {pattern}"
+    assert hb.heinsen_stream_probe_status(a, b, a, B, 100, D, 1, None) == hb.HEINSEN_ERR_UNSUPPORTED
