@@ -340,11 +340,14 @@ def flag_sweep(cfg, torch, hb, runs=30):
             ("POSITIVE (x in, x out)", hb.HEINSEN_POSITIVE | store),
             ("signed (x in, x out, signs tracked)", store),
             ("LINEAR (no logarithm or exponential at all)", hb.HEINSEN_LINEAR | store)]
-    lines = [f"workload cfg{cfg.index} {cfg.shape()} {cfg.layout}, {cfg.bytes_per_element} B/element, mean of {runs} launches after 40 untimed ones"]
+    lines = [f"workload cfg{cfg.index} {cfg.shape()} {cfg.layout}, {cfg.bytes_per_element} B/element, mean of {runs} launches after 50 ms of untimed ones"]
     for name, flags in sets:
         fn = lambda: hb.heinsen_scan(a, b, x0, out, cfg.B, cfg.D, cfg.n, layout, flags, stream)
-        for _ in range(40):
-            fn()
+        t0 = time.perf_counter()
+        while time.perf_counter() - t0 < 0.05:  # let the clocks settle (see time_workload)
+            for _ in range(20):
+                fn()
+            torch.cuda.synchronize()
         first, last = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
         first.record(stream)
         for _ in range(runs):

@@ -218,6 +218,75 @@ __device__ __forceinline__ void stash(const Seg &run, int k, float &r0, float &r
     }
 }
 
+// ---- a lane's serial scan --------------------------------------------------------------------------
+//
+// A lane owns T consecutive steps.  lane_step takes step k's stored inputs (in av, mv) and leaves the
+// element's record there (see stash); lane_close turns the running state into the summary (A, M) of the
+// lane's steps, which is what the log-space composition across lanes, waves and tiles works on.
+//
+// Two ways to run the steps inside the lane.  Log inputs and log outputs go through the log domain step by
+// step (seg_step: one signed log-add-exp per element, Sec. 4's LCSE).  Plain inputs with a plain output
+// need the zero-input response Z_k = sum_t b_t prod_{t<u<=k} a_u of the lane's steps in the linear domain
+// anyway (the record is (A_k, Z_k), and x_k = (+-)2^(lx + A_k) + Z_k, Eq. (3) with x_0 := the lane's start
+// state): there it is formed directly by the definition, Z_k = a_k Z_{k-1} + b_k (Sec. 3), one fused
+// multiply-add, while the first prefix sum A_k = sum log2|a_t| of Eq. (2) runs beside it.  Z_k has the
+// range of the outputs themselves (it is x_k for a lane that starts from 0), its signs are the floats'
+// own, and the element costs two transcendentals (log2|a_k|, and the exponential of the emit) instead of
+// six.  The lane's summary takes one more logarithm, M = log2|Z_T|.
+template <int DOM, bool LOG_IN, bool LOG_OUT>
+constexpr bool lane_is_direct()
+{
+    return DOM != kLinear && !LOG_IN && !LOG_OUT;
+}
+
+template <int DOM, bool LOG_IN, bool LOG_OUT>
+__device__ __forceinline__ void lane_step(int k, Seg &run, float &av, float &mv, uint32_t &sw, uint32_t &sm)
+{
+    constexpr bool SIGNED = DOM == kSigned;
+    if constexpr (lane_is_direct<DOM, LOG_IN, LOG_OUT>()) {
+        const float a = av, b = mv;
+        const float la = log2_hw(SIGNED ? fabsf(a) : a);
+        if (k == 0) {
+            run.A = la;
+            run.M = b; // Z_0 = b_0
+            run.sA = SIGNED ? f2u(a) : 0u;
+            run.sM = 0u;
+        } else {
+            run.M = fmaf(a, run.M, b); // Z_k = a_k Z_{k-1} + b_k
+            run.A += la;
+            if (SIGNED) run.sA ^= f2u(a);
+        }
+        av = run.A;
+        mv = run.M;
+        if (SIGNED) sw |= (run.sA >> 31) << k;
+        // Materialise the record here: left alone the optimiser keeps the inputs of many steps alive and
+        // forms the records late, which costs registers.
+        asm volatile("" : "+v"(av), "+v"(mv));
+        if (SIGNED) asm volatile("" : "+v"(sw));
+    } else {
+        float la, lb;
+        uint32_t sa, sb;
+        encode<DOM, LOG_IN>(av, la, sa);
+        encode<DOM, LOG_IN>(mv, lb, sb);
+        if (k == 0) {
+            run = Seg{la, lb, sa, sb};
+        } else {
+            seg_step<DOM>(run, la, sa, lb, sb);
+        }
+        stash<DOM, LOG_OUT>(run, k, av, mv, sw, sm);
+    }
+}
+
+template <int DOM, bool LOG_IN, bool LOG_OUT>
+__device__ __forceinline__ void lane_close(Seg &run)
+{
+    if constexpr (lane_is_direct<DOM, LOG_IN, LOG_OUT>()) {
+        const float z = run.M;
+        run.sM = DOM == kSigned ? f2u(z) : 0u;
+        run.M = log2_hw(fabsf(z));
+    }
+}
+
 // Folds the sign of the lane's start state into the sign word, once per lane.
 template <int DOM>
 __device__ __forceinline__ uint32_t fold_state_sign(uint32_t sw, const State &x)

@@ -32,18 +32,8 @@ __device__ __forceinline__ Seg lane_scan(float (&Av)[ITEMS], float (&Mv)[ITEMS],
     sw = sm = 0u;
     Seg run;
 #pragma unroll
-    for (int k = 0; k < ITEMS; ++k) {
-        float la, lb;
-        uint32_t sa, sb;
-        encode<DOM, LOG_IN>(Av[k], la, sa);
-        encode<DOM, LOG_IN>(Mv[k], lb, sb);
-        if (k == 0) {
-            run = Seg{la, lb, sa, sb};
-        } else {
-            seg_step<DOM>(run, la, sa, lb, sb);
-        }
-        stash<DOM, LOG_OUT>(run, k, Av[k], Mv[k], sw, sm);
-    }
+    for (int k = 0; k < ITEMS; ++k) lane_step<DOM, LOG_IN, LOG_OUT>(k, run, Av[k], Mv[k], sw, sm);
+    lane_close<DOM, LOG_IN, LOG_OUT>(run);
     return run;
 }
 

@@ -249,18 +249,10 @@ __device__ __forceinline__ void bnd_tile(const BndParams &p, const uint32_t tile
     Seg run;
 #pragma unroll
     for (int k = 0; k < T; ++k) {
-        float la, lb;
-        uint32_t sa, sb;
-        encode<DOM, LOG_IN>(Av[k], la, sa);
-        encode<DOM, LOG_IN>(Mv[k], lb, sb);
-        if (k == 0) {
-            run = Seg{la, lb, sa, sb};
-        } else {
-            seg_step<DOM>(run, la, sa, lb, sb);
-        }
-        stash<DOM, LOG_OUT>(run, k, Av[k], Mv[k], sw, sm);
+        lane_step<DOM, LOG_IN, LOG_OUT>(k, run, Av[k], Mv[k], sw, sm);
         if (SB) __builtin_amdgcn_sched_barrier(0);
     }
+    lane_close<DOM, LOG_IN, LOG_OUT>(run);
     p.tl.mark(tile, 2);
 
     // ---- the waves behind this one in the column need its summary --------------------------------
