@@ -271,6 +271,15 @@ def tile_timeline(cfg, torch, hb, launches=4):
     for i, nm in enumerate(names):
         d = t[:, i + 1] - t[:, i]
         lines.append(f"{nm:46s} {d.mean():7.2f} {np.median(d):7.2f} {np.percentile(d, 90):7.2f} {d.max():7.2f}")
+    if cfg.layout == "BDN" and cfg.B * cfg.D == 1:
+        # one row: tile i needs the summaries of all tiles before it.  How long after the last of them was
+        # handed on does tile i know its start state?  (the latency of the carry tree itself, as opposed to
+        # waiting for predecessors that are still loading)
+        handed = np.maximum.accumulate(t[:, 3])
+        lag = (t[:, 5] - np.maximum(handed, t[:, 3]))[1:]
+        own = (handed - t[:, 3])[1:]
+        lines.append(f"{'own summary -> summary of the last predecessor':46s} {own.mean():7.2f} {np.median(own):7.2f} {np.percentile(own, 90):7.2f} {own.max():7.2f}")
+        lines.append(f"{'all summaries handed on -> start state known':46s} {lag.mean():7.2f} {np.median(lag):7.2f} {np.percentile(lag, 90):7.2f} {lag.max():7.2f}")
     life = t[:, 7] - t[:, 0]
     lines.append(f"{'tile life (start -> end)':46s} {life.mean():7.2f} {np.median(life):7.2f} {np.percentile(life, 90):7.2f} {life.max():7.2f}")
     starts, ends = np.sort(t[:, 0]), np.sort(t[:, 7])
@@ -315,11 +324,19 @@ def stream_probe(cfg, torch, hb, runs=20):
              "256 x 64, stores after all loads"]
     lines = [f"out = a + b on [B={B}, n={n}, D={D}] float32 ({12 * E / 1e6:.0f} MB per launch), mean of {runs} launches after 40 untimed ones"]
     for pat, nm in enumerate(names):
+        if cfg.layout == "BDN" and pat > 0:
+            continue  # the tile patterns are those of the [B, n, D] kernel
         if hb.heinsen_stream_probe_status(a, b, out, B, n, D, pat, stream) != hb.HEINSEN_OK:
             lines.append(f"  heinsen_stream_probe {pat}: {nm:44s} not applicable to this shape")
             continue
         us, gbs = timed(lambda: hb.heinsen_stream_probe_status(a, b, out, B, n, D, pat, stream), 12 * E)
         lines.append(f"  heinsen_stream_probe {pat}: {nm:44s} {us:8.1f} us  {gbs:6.0f} GB/s  {gbs / HBM_PEAK_GBS:.3f} of peak")
+    if cfg.bf16:
+        ah, bh = a.to(torch.bfloat16), b.to(torch.bfloat16)
+        us, gbs = timed(lambda: hb.heinsen_stream_probe_status(ah, bh, out, B, n, D, 7, stream), 8 * E)
+        lines.append(f"  heinsen_stream_probe 7: {'one long vector, bf16 in, float32 out (8 B/element)':44s} {us:8.1f} us  {gbs:6.0f} GB/s  "
+                     f"{gbs / HBM_PEAK_GBS:.3f} of peak")
+        del ah, bh
     us, gbs = timed(lambda: torch.add(a, b, out=out), 12 * E)
     lines.append(f"  torch.add(a, b, out=o)  {'':47s} {us:8.1f} us  {gbs:6.0f} GB/s  {gbs / HBM_PEAK_GBS:.3f} of peak")
     us, gbs = timed(lambda: out.copy_(a), 8 * E)

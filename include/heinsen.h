@@ -193,8 +193,10 @@ int heinsen_sequential(const void *a, const void *b, const void *x0, void *out, 
  * beside the published peak.  pattern: 0 the array as one long vector, 16 bytes per lane; 1 the default
  * tile of the [B, n, D] kernel (workgroup = 64 channels x 256 steps, rows of 256 bytes); 2 its wide tile
  * (128 channels x 128 steps, rows of 512 bytes); 3 256 channels x 64 steps; 4, 5, 6 = 1, 2, 3 with no output
- * stored before all of a lane's inputs have arrived, as in a scan.  Patterns 1..6 need D a multiple of
- * 64, 128, 256 and n a multiple of 256, 128, 64 (HEINSEN_ERR_UNSUPPORTED otherwise).  Asynchronous on
+ * stored before all of a lane's inputs have arrived, as in a scan; 7 as 0 with a and b stored as bf16
+ * (B*n*D elements of 2 bytes each, 8-byte aligned; out float32): the traffic mix of bf16 storage, one
+ * byte read per byte written.  Patterns 1..6 need D a multiple of 64, 128, 256 and n a multiple of 256,
+ * 128, 64, patterns 0 and 7 B*n*D a multiple of 4 (HEINSEN_ERR_UNSUPPORTED otherwise).  Asynchronous on
  * `stream`.  Returns a heinsen_status_t.
  */
 int heinsen_stream_probe(const void *a, const void *b, void *out, int64_t B, int64_t n, int64_t D, int pattern,

@@ -16,6 +16,32 @@ __global__ __launch_bounds__(256) void heinsen_probe_linear(const f4 *a, const f
     if (i < n4) __builtin_nontemporal_store(__builtin_nontemporal_load(a + i) + __builtin_nontemporal_load(b + i), o + i);
 }
 
+// pattern 7: bf16 inputs widened to a float32 output (4 bytes read, 4 written per element: the mix of
+// traffic of a scan with bf16 storage), one long vector; a lane takes 4 elements at a time (8 bytes from
+// each input, 16 bytes out, so that every access of a wave is one contiguous piece), two such per lane
+typedef unsigned int u2 __attribute__((ext_vector_type(2)));
+__global__ __launch_bounds__(256) void heinsen_probe_linear_bf16(const u2 *a, const u2 *b, f4 *o, size_t n4)
+{
+    const size_t i0 = (size_t)blockIdx.x * 512 + threadIdx.x;
+    u2 x[2], y[2];
+#pragma unroll
+    for (int k = 0; k < 2; ++k)
+        if (i0 + k * 256 < n4) {
+            x[k] = __builtin_nontemporal_load(a + i0 + k * 256);
+            y[k] = __builtin_nontemporal_load(b + i0 + k * 256);
+        }
+#pragma unroll
+    for (int k = 0; k < 2; ++k)
+        if (i0 + k * 256 < n4) {
+            f4 r;
+            r[0] = __uint_as_float(x[k][0] << 16) + __uint_as_float(y[k][0] << 16);
+            r[1] = __uint_as_float(x[k][0] & 0xffff0000u) + __uint_as_float(y[k][0] & 0xffff0000u);
+            r[2] = __uint_as_float(x[k][1] << 16) + __uint_as_float(y[k][1] << 16);
+            r[3] = __uint_as_float(x[k][1] & 0xffff0000u) + __uint_as_float(y[k][1] & 0xffff0000u);
+            __builtin_nontemporal_store(r, o + i0 + k * 256);
+        }
+}
+
 // patterns 1..3: a workgroup of CG x TS waves takes 64*CG adjacent channels for TS*32 steps; a lane owns one
 // channel for 32 steps (the tiles of the [B, n, D] scan kernel: CG = 1 and CG = 2; CG = 4 for comparison).
 // SEP: no output is stored before all of the lane's inputs have arrived, as in a scan.
@@ -61,6 +87,13 @@ extern "C" int heinsen_stream_probe(const void *a, const void *b, void *out, int
         const size_t n4 = (size_t)(B * n * D) / 4;
         hipLaunchKernelGGL(heinsen_probe_linear, dim3((unsigned)((n4 + 255) / 256)), dim3(256), 0, stream,
                            reinterpret_cast<const f4 *>(pa), reinterpret_cast<const f4 *>(pb), reinterpret_cast<f4 *>(po), n4);
+        return hipGetLastError() == hipSuccess ? HEINSEN_OK : HEINSEN_ERR_HIP;
+    }
+    if (pattern == 7) {
+        if ((B * n * D) % 4 != 0) return HEINSEN_ERR_UNSUPPORTED;
+        const size_t n4 = (size_t)(B * n * D) / 4;
+        hipLaunchKernelGGL(heinsen_probe_linear_bf16, dim3((unsigned)((n4 + 511) / 512)), dim3(256), 0, stream,
+                           static_cast<const u2 *>(a), static_cast<const u2 *>(b), reinterpret_cast<f4 *>(po), n4);
         return hipGetLastError() == hipSuccess ? HEINSEN_OK : HEINSEN_ERR_HIP;
     }
     const int cg = pattern == 1 || pattern == 4 ? 1 : (pattern == 2 || pattern == 5 ? 2 : 4);

@@ -124,4 +124,9 @@ def test_stream_probe_adds(gpu):
         assert hb.heinsen_stream_probe_status(a, b, out, B, n, D, pattern, torch.cuda.current_stream()) == hb.HEINSEN_OK
         torch.cuda.synchronize()
         assert torch.equal(out, a + b), f"pattern {pattern}"
+    ah, bh = a.to(torch.bfloat16), b.to(torch.bfloat16)
+    out = torch.zeros_like(a)
+    assert hb.heinsen_stream_probe_status(ah, bh, out, B, n, D, 7, torch.cuda.current_stream()) == hb.HEINSEN_OK
+    torch.cuda.synchronize()
+    assert torch.equal(out, ah.float() + bh.float()), "pattern 7"
     assert hb.heinsen_stream_probe_status(a, b, a, B, 100, D, 1, None) == hb.HEINSEN_ERR_UNSUPPORTED
