@@ -19,7 +19,7 @@ FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-u
 
 def _compile(src: str) -> str:
     obj = os.path.join(CSRC, os.path.splitext(src)[0] + ".o")
-    extra = os.environ.get("HEINSEN_EXTRA_HIPCC_FLAGS", "").split()  # e.g. -DHS_TUNING for development builds
+    extra = os.environ.get("HEINSEN_EXTRA_HIPCC_FLAGS", "").split()  # extra compiler flags for development builds
     cmd = [HIPCC, *FLAGS, *extra, "-c", os.path.join(CSRC, src), "-o", obj]
     r = subprocess.run(cmd, capture_output=True, text=True)
     noise = "is not a recognized feature for this target"
