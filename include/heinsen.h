@@ -174,6 +174,13 @@ int heinsen_release_scratch(void);
 /* Name of the kernel heinsen_scan would launch for these arguments (for profilers), written as a
  * NUL-terminated string into buf (at most buflen bytes).  Launches nothing.  Returns a
  * heinsen_status_t from the same validation heinsen_scan performs (pointers are not checked). */
+/* The piece of the problem one workgroup of that kernel takes ("tile"): `sequences` adjacent sequences
+ * (channels of [B, n, D], rows of [B, D, n]) for `steps` consecutive steps (the last tile of a sequence may
+ * be shorter).  For profilers and for reading the tile ids of heinsen_set_timeline.  Launches nothing.
+ * Returns a heinsen_status_t from the same validation heinsen_scan performs (pointers are not checked). */
+int heinsen_tile_shape(int64_t B, int64_t D, int64_t n, int layout, uint32_t flags, int *sequences,
+                       int64_t *steps);
+
 int heinsen_kernel_name(int64_t B, int64_t D, int64_t n, int layout, uint32_t flags, char *buf,
                         int buflen);
 

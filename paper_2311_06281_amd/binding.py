@@ -36,7 +36,7 @@ HEINSEN_ERR_SCRATCH_LIMIT = 5
 HEINSEN_ERR_CARRY_LOST = 6
 
 EXPORTS = ("heinsen_scan", "heinsen_scan_static", "heinsen_status_string", "heinsen_last_hip_error", "heinsen_version",
-           "heinsen_release_scratch", "heinsen_kernel_name", "heinsen_sequential", "heinsen_check",
+           "heinsen_release_scratch", "heinsen_kernel_name", "heinsen_tile_shape", "heinsen_sequential", "heinsen_check",
            "heinsen_set_timeline", "heinsen_test_carry", "heinsen_stream_probe")
 
 _lib = None
@@ -70,6 +70,8 @@ def load() -> ctypes.CDLL:
         lib.heinsen_release_scratch.restype = ci
         lib.heinsen_kernel_name.argtypes = [i64, i64, i64, ci, u32, ctypes.c_char_p, ci]
         lib.heinsen_kernel_name.restype = ci
+        lib.heinsen_tile_shape.argtypes = [i64, i64, i64, ci, u32, ctypes.POINTER(ci), ctypes.POINTER(i64)]
+        lib.heinsen_tile_shape.restype = ci
         lib.heinsen_check.argtypes = [vp]
         lib.heinsen_check.restype = ci
         lib.heinsen_set_timeline.argtypes = [vp, ctypes.c_uint64]
@@ -130,6 +132,15 @@ def heinsen_kernel_name(B: int, D: int, n: int, layout: int, flags: int) -> str:
     if st != HEINSEN_OK:
         raise HeinsenError(st, heinsen_status_string(st))
     return buf.value.decode()
+
+
+def heinsen_tile_shape(B: int, D: int, n: int, layout: int, flags: int):
+    """(adjacent sequences, consecutive steps) of the tile one workgroup takes; see include/heinsen.h."""
+    seqs, steps = ctypes.c_int(0), ctypes.c_int64(0)
+    st = load().heinsen_tile_shape(B, D, n, layout, flags, ctypes.byref(seqs), ctypes.byref(steps))
+    if st != HEINSEN_OK:
+        raise HeinsenError(st, heinsen_status_string(st))
+    return seqs.value, steps.value
 
 
 def heinsen_scan_status(a, b, x0, out, B: int, D: int, n: int, layout: int, flags: int, stream=None) -> int:

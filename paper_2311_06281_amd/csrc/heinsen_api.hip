@@ -366,4 +366,16 @@ int heinsen_kernel_name(int64_t B, int64_t D, int64_t n, int layout, uint32_t fl
     return HEINSEN_OK;
 }
 
+int heinsen_tile_shape(int64_t B, int64_t D, int64_t n, int layout, uint32_t flags, int *sequences, int64_t *steps)
+{
+    if (!sequences || !steps) return HEINSEN_ERR_INVALID_ARG;
+    hs::ScanCall c = {};
+    bool bnd = false;
+    int st = describe(B, D, n, layout, flags, c, bnd);
+    if (st != HEINSEN_OK) return st;
+    if (bnd) hs::bnd_tile_shape(c, *sequences, *steps);
+    else hs::bdn_tile_shape(c, *sequences, *steps);
+    return HEINSEN_OK;
+}
+
 } // extern "C"

@@ -61,10 +61,12 @@ struct ScratchNeed {
 ScratchNeed bnd_scratch(const ScanCall &c);
 hipError_t bnd_launch(const ScanCall &c, const LaunchCtx &ctx);
 const char *bnd_kernel_name(const ScanCall &c);
+void bnd_tile_shape(const ScanCall &c, int &channels, int64_t &steps); // of one workgroup
 
 ScratchNeed bdn_scratch(const ScanCall &c);
 hipError_t bdn_launch(const ScanCall &c, const LaunchCtx &ctx);
 const char *bdn_kernel_name(const ScanCall &c);
+void bdn_tile_shape(const ScanCall &c, int &rows, int64_t &steps); // of one workgroup
 
 static inline int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
 static inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }

@@ -871,4 +871,17 @@ const char *bdn_kernel_name(const ScanCall &c)
     return "heinsen_scan_tiles";
 }
 
+void bdn_tile_shape(const ScanCall &c, int &rows, int64_t &steps)
+{
+    const BdnPlan pl = make_plan(c);
+    if (pl.wave_kernel) {
+        // one wave per row, or 64 / group rows per wave; workgroups of four waves
+        rows = pl.group > 0 ? 4 * (64 / pl.group) : 4;
+        steps = c.n;
+    } else {
+        rows = 1;
+        steps = (int64_t)kTileWaves * 64 * pl.tile_items;
+    }
+}
+
 } // namespace hs

@@ -763,4 +763,11 @@ hipError_t bnd_launch(const ScanCall &c, const LaunchCtx &ctx)
 
 const char *bnd_kernel_name(const ScanCall &) { return "heinsen_scan_bnd"; }
 
+void bnd_tile_shape(const ScanCall &c, int &channels, int64_t &steps)
+{
+    const BndPlan pl = make_plan(c);
+    channels = pl.bpack > 1 ? (int)c.D : pl.CH; // narrow rows: the channels of pl.bpack batch items side by side
+    steps = (int64_t)(pl.NW / pl.cg) * pl.T;
+}
+
 } // namespace hs

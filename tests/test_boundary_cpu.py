@@ -70,6 +70,18 @@ def test_bad_arguments_are_rejected_on_the_host(args, expect):
     assert hb.heinsen_scan_status(*args) == expect
 
 
+def test_tile_shape_of_the_benchmark_workloads():
+    assert hb.heinsen_tile_shape(16, 2048, 16384, hb.HEINSEN_LAYOUT_BND, 0) == (128, 128)  # wide tile
+    assert hb.heinsen_tile_shape(8, 1024, 4096, hb.HEINSEN_LAYOUT_BND, 0) == (64, 256)
+    assert hb.heinsen_tile_shape(2, 16384, 1229, hb.HEINSEN_LAYOUT_BND, hb.HEINSEN_POSITIVE) == (128, 128)
+    assert hb.heinsen_tile_shape(2, 16384, 1000, hb.HEINSEN_LAYOUT_BND, 0) == (64, 256)    # too short for the wide tile
+    assert hb.heinsen_tile_shape(1, 1, 1 << 26, hb.HEINSEN_LAYOUT_BDN, 8) == (1, 16384)
+    assert hb.heinsen_tile_shape(1, 1, 4096, hb.HEINSEN_LAYOUT_BDN, 8) == (1, 4096)
+    assert hb.heinsen_tile_shape(64, 4096, 2048, hb.HEINSEN_LAYOUT_BDN, 7) == (4, 2048)
+    with pytest.raises(hb.HeinsenError):
+        hb.heinsen_tile_shape(1, 1, 0, 0, 0)
+
+
 def test_kernel_name_follows_layout_and_length():
     assert hb.heinsen_kernel_name(8, 1024, 4096, hb.HEINSEN_LAYOUT_BND, 0) == "heinsen_scan_bnd"
     assert hb.heinsen_kernel_name(64, 4096, 2048, hb.HEINSEN_LAYOUT_BDN, 7) == "heinsen_scan_rows_wave"

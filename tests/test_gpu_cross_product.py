@@ -141,6 +141,26 @@ def test_every_mode_layout_and_storage_type(gpu, layout, mode, bf16):
         _check(got, a, b, x0, layout, mode)
 
 
+# [B, n, D] with at least 256 columns of 128 channels and n >= 1024 takes the wide tile (two waves side by
+# side, 128 steps per tile): a ragged tail (9 tiles and 77 steps: two waves and a half of the last tile have
+# steps, the other one and a half have none) and a last column that ends with the array
+@pytest.mark.parametrize("mode,bf16", [(m, False) for m in MODES] + [("signed", True), ("log_logout", True)])
+def test_wide_tiles_every_mode(gpu, mode, bf16):
+    torch, hb = gpu
+    shape = (2, 1024 + 205, 16384)
+    flags = hb.flags_from_names(MODES[mode]) | (hb.HEINSEN_IN_BF16 if bf16 else 0)
+    tile = hb.heinsen_tile_shape(shape[0], shape[2], shape[1], hb.HEINSEN_LAYOUT_BND, flags)
+    assert tile == ((64, 256) if mode == "signed_clog" else (128, 128))  # the complex output has a tile of its own
+    print(f"[wide] {mode} bf16={bf16} shape={shape} tile={tile}", flush=True)
+    rng = np.random.default_rng(4100 + sum(ord(ch) for ch in mode) + int(bf16))
+    a, b, x0 = _inputs(rng, shape, "BND", mode)
+    if bf16:
+        a = workloads.bf16_bits_to_f32(workloads.f32_to_bf16_bits(a)).reshape(shape)
+        b = workloads.bf16_bits_to_f32(workloads.f32_to_bf16_bits(b)).reshape(shape)
+    got = _run(gpu, a, b, x0, "BND", MODES[mode], bf16)
+    _check(got, a, b, x0, "BND", mode)
+
+
 @pytest.mark.parametrize("layout,shape", [("BDN", (2, 3, 2048)), ("BDN", (1, 2, 16384 * 2 + 16)), ("BND", (1, 300, 128)), ("BND", (2, 64, 66))])
 @pytest.mark.parametrize("bf16", [False, True])
 @pytest.mark.parametrize("offset", [1, 2, 3])
