@@ -36,7 +36,8 @@ def _run(cfg, dev, torch, hb, static=False):
 CHAINED = [
     workloads.CONFIGS[2].scaled(B=1, D=128, n=2048),   # [B, n, D]: 2 columns x 8 tiles, two groups
     workloads.CONFIGS[2].scaled(B=1, D=64, n=40000),   # one column: second carry level
-    workloads.CONFIGS[3].scaled(n=16384 * 40 + 5),     # one row of 41 tiles: two-level tree
+    workloads.CONFIGS[3].scaled(n=16384 * 40 + 5),     # one row of 81 half tiles (8192 steps): two-level tree
+    workloads.CONFIGS[3].scaled(n=16384 * 140 + 5),    # one row of 141 full tiles (16384 steps)
 ]
 
 
@@ -57,15 +58,19 @@ def test_launch_counter_comes_round(gpu, cfg, static):
     assert hb.heinsen_check(stream) == hb.HEINSEN_OK
 
 
-@pytest.mark.parametrize("cfg,drop,first_bad", [
-    # tile 2 = chunk 1 of column 0 never publishes: chunks 2 and 3 of its group wait in vain; 256 steps per tile
-    (CHAINED[0], 2, 2 * 256),
-    # tile 3 of the row never publishes: every later tile folds it; 16384 steps per tile
-    (CHAINED[2], 3, 4 * 16384),
+@pytest.mark.parametrize("cfg,drop,bad_from_tile", [
+    # tile 2 = chunk 1 of column 0 never publishes: chunks 2 and 3 of its group wait in vain
+    (CHAINED[0], 2, 2),
+    # tile 3 of the row never publishes: every later tile folds it
+    (CHAINED[2], 3, 4),
+    (CHAINED[3], 3, 4),
 ])
-def test_lost_carry_ends_in_nan_and_a_report(gpu, cfg, drop, first_bad):
+def test_lost_carry_ends_in_nan_and_a_report(gpu, cfg, drop, bad_from_tile):
     torch, hb = gpu
     stream = torch.cuda.current_stream()
+    steps = hb.heinsen_tile_shape(cfg.B, cfg.D, cfg.n, hb.LAYOUTS[cfg.layout], hb.flags_from_names(cfg.flags))[1]
+    assert steps == {0: 256, 2: 8192, 3: 16384}[CHAINED.index(cfg)]
+    first_bad = bad_from_tile * steps
     dev = to_device(workloads.generate(cfg), cfg, torch)
     want = _run(cfg, dev, torch, hb)
     assert hb.heinsen_check(stream) == hb.HEINSEN_OK

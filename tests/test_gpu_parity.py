@@ -50,7 +50,7 @@ def test_cfg2_scaled(gpu, B, D, n):
 
 
 # ---- configuration 3: one long sequence (tiles chained through global memory) -------------------------------
-@pytest.mark.parametrize("n", [16384 * 3, 16384 * 75 + 8, 16384 * 300 + 1])  # 3 tiles; 3 groups of 32 tiles; 10 groups
+@pytest.mark.parametrize("n", [16384 * 3, 16384 * 75 + 8, 16384 * 300 + 1])  # 6 half tiles; 3 groups of 32 tiles; 10 groups
 def test_cfg3_scaled(gpu, n):
     _check(workloads.CONFIGS[3].scaled(n=n), gpu, f"cfg3 n={n}")
 
