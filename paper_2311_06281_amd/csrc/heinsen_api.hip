@@ -329,7 +329,7 @@ const char *heinsen_status_string(int status)
 
 int heinsen_last_hip_error(void) { return t_last_hip_error; }
 
-int heinsen_version(void) { return 300; /* 0.3.0: heinsen_scan_static, heinsen_check, heinsen_set_timeline */ }
+int heinsen_version(void) { return 301; /* 0.3.1: 0.3.0 (heinsen_scan_static, heinsen_check, heinsen_set_timeline) + heinsen_tile_shape */ }
 
 int heinsen_release_scratch(void)
 {
